@@ -1,0 +1,241 @@
+"""CPU checker for the DiLoCo optimizer sweep.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, single-threaded float64 NumPy statement of what the hot path
+computes: the inner AdamW step (line 5 of Algorithms 1-3), the standard outer
+step (Algorithm 1, lines 7-10), the naive delayed outer step (Algorithm 2,
+lines 7-11) and the eager outer step (Algorithm 3, lines 7-12), plus the noisy
+quadratic used as a stand-in training problem.  It shares no code with the HIP
+library and is imported only by the tests, by the smoke check and by the
+benchmark's cpu_baseline leg.  Nothing in the product path may call it.
+
+The method is a sequence of arithmetic updates with no independent definition,
+so this file follows the algorithms' steps in the paper's order and notation:
+
+    theta_m       live parameters of replica m                     theta[m, :]
+    theta_m^(t-H) outer parameters ("anchor") of replica m         a[m, :] or a[:]
+    Delta_m^(t)   fresh local outer gradient                       delta[m, :]
+    Delta^(t)     its mean over replicas                           delta_bar[:]
+    Delta_m^(t-H) previous local outer gradient                    P[m, :]
+    Delta^(t-H)   previous averaged outer gradient                 D[:]
+    OuterOpt      SGD with Nesterov momentum, velocity             u
+    InnerOpt      AdamW, moments                                   m1, m2
+
+Readings where the paper gives no formula (Section 2 names the optimizers
+only): AdamW is the decoupled-weight-decay, bias-corrected form with epsilon
+added outside the square root; Nesterov momentum is the velocity form
+u <- mu u + G, a <- a - eta (G + mu u).  Every function mutates its array
+arguments in place and all arrays are float64.
+
+Parity pins (tests/test_oracle_pins.py): closed forms for constant gradients,
+torch.optim.SGD / torch.optim.AdamW in float64 as black boxes on whole
+trajectories, the paper's equivalent form of the eager combination (Section
+2.3: the mean of the fresh local and the stale non-local outer gradients),
+M = 1 and identical-worker reductions, the mu = 0, eta = 1 worker average, and
+published splitmix64 test vectors plus distribution tests for the noise.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+U64 = np.uint64
+
+
+# --------------------------------------------------------------------------
+# InnerOpt: AdamW (Algorithms 1-3, line 5)
+# --------------------------------------------------------------------------
+def adamw_step(theta, m1, m2, g, t, lr, beta1, beta2, eps, weight_decay):
+    """One AdamW step, t >= 1 is the global step count (never reset).
+
+    m1 <- b1 m1 + (1-b1) g ; m2 <- b2 m2 + (1-b2) g^2 ;
+    theta <- theta - lr ( m1_hat / (sqrt(m2_hat) + eps) + wd * theta ),
+    with m_hat = m / (1 - b^t) and the decay term using theta before the step.
+    """
+    assert t >= 1
+    m1[...] = beta1 * m1 + (1.0 - beta1) * g
+    m2[...] = beta2 * m2 + (1.0 - beta2) * (g * g)
+    m1_hat = m1 / (1.0 - beta1 ** t)
+    m2_hat = m2 / (1.0 - beta2 ** t)
+    theta[...] = theta - lr * (m1_hat / (np.sqrt(m2_hat) + eps) + weight_decay * theta)
+
+
+# --------------------------------------------------------------------------
+# OuterOpt: SGD with (Nesterov) momentum (Algorithm 1 line 10, 2 line 11, 3 line 12)
+# --------------------------------------------------------------------------
+def nesterov_step(a, u, G, eta, mu, nesterov=True):
+    """u <- mu u + G ; a <- a - eta (G + mu u) (Nesterov) or a <- a - eta u (heavy ball)."""
+    u[...] = mu * u + G
+    if nesterov:
+        a[...] = a - eta * (G + mu * u)
+    else:
+        a[...] = a - eta * u
+
+
+def local_outer_gradients(a, theta):
+    """Line 7: Delta_m = theta_m^(t-H) - theta_m^(t).  `a` is [n] (shared) or [M, n]."""
+    return a - theta  # broadcasting covers the shared anchor
+
+
+def mean_over_replicas(delta):
+    """Line 8: Delta = (1/M) sum_m Delta_m, summed left to right in m."""
+    M = delta.shape[0]
+    s = delta[0].copy()
+    for m in range(1, M):
+        s += delta[m]
+    return s / M
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1: standard DiLoCo, one shared set of outer parameters
+# --------------------------------------------------------------------------
+def outer_standard(theta, a, u, eta, mu, nesterov=True):
+    """theta [M, n]; a, u [n] shared by all replicas.  Returns Delta^(t)."""
+    delta = local_outer_gradients(a, theta)          # line 7
+    delta_bar = mean_over_replicas(delta)            # lines 8-9
+    nesterov_step(a, u, delta_bar, eta, mu, nesterov)  # line 10
+    theta[...] = a                                    # every replica restarts from the outer params
+    return delta_bar
+
+
+# --------------------------------------------------------------------------
+# Algorithm 2: naive delayed outer gradients, per-replica outer parameters
+# --------------------------------------------------------------------------
+def outer_delayed(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True):
+    """theta, a, u, P [M, n]; D [n].  apply_update=False is the t = H boundary,
+    where the listing applies no outer step: the replica just continues from its
+    own parameters, which become its next anchor."""
+    delta = local_outer_gradients(a, theta)          # line 7
+    delta_bar = mean_over_replicas(delta)            # line 8 (arrives one phase later)
+    if apply_update:                                 # line 9: t > H
+        for m in range(theta.shape[0]):
+            nesterov_step(a[m], u[m], D, eta, mu, nesterov)   # lines 10-11 with Delta^(t-H)
+    else:
+        a[...] = theta
+    theta[...] = a
+    P[...] = delta
+    D[...] = delta_bar
+
+
+# --------------------------------------------------------------------------
+# Algorithm 3: eager updates with delayed outer gradients
+# --------------------------------------------------------------------------
+def eager_combination(delta, P, D):
+    """Line 11: Delta~_m = (1/M)(Delta_m^(t) - Delta_m^(t-H)) + Delta^(t-H)."""
+    M = delta.shape[0]
+    return (delta - P) / M + D
+
+
+def outer_eager(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True):
+    """theta, a, u, P [M, n]; D [n].  All Delta~_m are formed from the old P and D
+    before either is overwritten."""
+    delta = local_outer_gradients(a, theta)          # line 7
+    delta_bar = mean_over_replicas(delta)            # line 8
+    if apply_update:                                 # line 9: t > H
+        G = eager_combination(delta, P, D)           # lines 10-11
+        for m in range(theta.shape[0]):
+            nesterov_step(a[m], u[m], G[m], eta, mu, nesterov)  # line 12
+    else:
+        a[...] = theta
+    theta[...] = a
+    P[...] = delta
+    D[...] = delta_bar
+
+
+def reset(theta, a):
+    """theta_m <- outer parameters (shared [n] or per replica [M, n])."""
+    theta[...] = a
+
+
+# --------------------------------------------------------------------------
+# Noisy quadratic stand-in problem: loss 0.5 sum_i h_i (theta_i - theta*_i)^2
+# --------------------------------------------------------------------------
+_GOLDEN = U64(0x9E3779B97F4A7C15)
+
+
+def mix64(x):
+    """Output function of the splitmix64 generator (Steele, Lea, Flood 2014) on uint64 arrays."""
+    x = np.asarray(x, dtype=U64).copy()
+    with np.errstate(over="ignore"):
+        x ^= x >> U64(30)
+        x *= U64(0xBF58476D1CE4E5B9)
+        x ^= x >> U64(27)
+        x *= U64(0x94D049BB133111EB)
+        x ^= x >> U64(31)
+    return x
+
+
+def noise_key(seed, t, m):
+    """Stream key of (seed, step t, replica m): two chained splitmix64 outputs."""
+    with np.errstate(over="ignore"):
+        k0 = mix64(U64(seed) + _GOLDEN * U64(t + 1))
+        return mix64(k0 + _GOLDEN * U64(m + 1))
+
+
+def standard_normal(seed, t, m, idx):
+    """z(seed, t, m, i) for int64 indices `idx`: elements 2j and 2j+1 share the 64-bit word
+    x_j = splitmix64 output number j of the stream keyed by (seed, t, m);
+    u1 = (top 24 bits + 1) / 2^24 in (0, 1], u2 = (next 24 bits) / 2^24 in [0, 1);
+    Box-Muller: z_2j = r cos(2 pi u2), z_2j+1 = r sin(2 pi u2), r = sqrt(-2 ln u1)."""
+    idx = np.asarray(idx, dtype=np.int64)
+    j = (idx >> 1).astype(U64)
+    with np.errstate(over="ignore"):
+        x = mix64(noise_key(seed, t, m) + _GOLDEN * (j + U64(1)))
+    u1 = ((x >> U64(40)).astype(F64) + 1.0) / 16777216.0
+    u2 = ((x >> U64(16)) & U64(0xFFFFFF)).astype(F64) / 16777216.0
+    r = np.sqrt(-2.0 * np.log(u1))
+    ang = 2.0 * np.pi * u2
+    return np.where((idx & 1) == 0, r * np.cos(ang), r * np.sin(ang))
+
+
+def quadratic_gradient(theta_m, h, theta_star, noise_std, seed, t, m, index_base=0):
+    """g_m = h (theta_m - theta*) + noise_std z(seed, t, m, i), i = index_base + position."""
+    idx = index_base + np.arange(theta_m.shape[-1], dtype=np.int64)
+    return h * (theta_m - theta_star) + noise_std * standard_normal(seed, t, m, idx)
+
+
+def quadratic_loss(theta, h, theta_star):
+    """0.5 sum_i h_i (theta_i - theta*_i)^2 for one parameter vector [n]."""
+    d = theta - theta_star
+    return 0.5 * float(np.sum(h * d * d))
+
+
+def quadratic_inner_step(theta, m1, m2, h, theta_star, t, seed, noise_std,
+                         lr, beta1, beta2, eps, weight_decay, index_base=0):
+    """Lines 3-5 on the quadratic: every replica takes one AdamW step on its own noisy gradient."""
+    for m in range(theta.shape[0]):
+        g = quadratic_gradient(theta[m], h, theta_star, noise_std, seed, t, m, index_base)
+        adamw_step(theta[m], m1[m], m2[m], g, t, lr, beta1, beta2, eps, weight_decay)
+
+
+# --------------------------------------------------------------------------
+# Drivers: whole runs of Algorithms 1-3
+# --------------------------------------------------------------------------
+def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
+                  lr, beta1, beta2, eps, weight_decay, eta, mu, nesterov=True,
+                  index_base=0, theta0=None):
+    """T = H * phases steps of Algorithm 1 ("standard"), 2 ("delayed") or 3 ("eager")
+    on the noisy quadratic, starting from theta = theta0 (default 0) on every replica.
+    Returns (state dict, losses) with losses[k] the loss after outer boundary k,
+    evaluated at the replica mean of the outer parameters."""
+    n = h.shape[0]
+    theta = np.zeros((M, n), F64) if theta0 is None else np.tile(np.asarray(theta0, F64), (M, 1))
+    m1 = np.zeros((M, n), F64)
+    m2 = np.zeros((M, n), F64)
+    shared = variant == "standard"
+    a = theta[0].copy() if shared else theta.copy()
+    u = np.zeros_like(a)
+    P = np.zeros((M, n), F64)
+    D = np.zeros(n, F64)
+    losses = []
+    for t in range(1, H * phases + 1):
+        quadratic_inner_step(theta, m1, m2, h, theta_star, t, seed, noise_std,
+                             lr, beta1, beta2, eps, weight_decay, index_base)
+        if t % H == 0:
+            if variant == "standard":
+                outer_standard(theta, a, u, eta, mu, nesterov)
+                losses.append(quadratic_loss(a, h, theta_star))
+            else:
+                step = outer_eager if variant == "eager" else outer_delayed
+                step(theta, a, u, P, D, eta, mu, nesterov, apply_update=(t > H))
+                losses.append(quadratic_loss(mean_over_replicas(a), h, theta_star))
+    return dict(theta=theta, a=a, u=u, P=P, D=D, m1=m1, m2=m2), losses

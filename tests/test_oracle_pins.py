@@ -1,0 +1,456 @@
+"""Pins of the CPU checker against what the paper and the mathematics fix.
+
+None of these tests re-types the checker's own formulas: they use closed
+forms, torch.optim.SGD / torch.optim.AdamW in float64 as black boxes, the
+paper's second way of writing the eager combination (Section 2.3: the mean of
+the fresh local and all stale non-local outer gradients), reductions the
+listings imply (M = 1, identical replicas, stationary outer gradients), and
+published generator outputs.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+from scipy import stats
+
+from oracle import diloco_oracle as O
+
+RNG = np.random.default_rng(20250212996)
+
+
+def rnd(*shape, scale=1.0):
+    return RNG.standard_normal(shape) * scale
+
+
+# ----------------------------------------------------------------- AdamW ---
+def test_adamw_constant_gradient_closed_form():
+    # constant g != 0 from zero moments: m1_hat = g and m2_hat = g^2 at every t, so
+    # theta_t = theta_{t-1} (1 - lr wd) - lr g / (|g| + eps)
+    lr, b1, b2, eps, wd = 4e-4, 0.9, 0.95, 1e-8, 0.1
+    g = np.array([0.3, -2.0, 1e-3, 7.0])
+    th = np.array([0.5, -0.25, 1.0, 0.0])
+    m1 = np.zeros(4)
+    m2 = np.zeros(4)
+    want = th.copy()
+    for t in range(1, 40):
+        O.adamw_step(th, m1, m2, g, t, lr, b1, b2, eps, wd)
+        want = want * (1 - lr * wd) - lr * g / (np.abs(g) + eps)
+        np.testing.assert_allclose(th, want, rtol=1e-12, atol=1e-15)
+
+
+def test_adamw_first_step_is_sign_step():
+    lr = 1e-2
+    g = np.array([5.0, -1e-4, 3.0])
+    th = np.array([1.0, 2.0, -3.0])
+    th0 = th.copy()
+    O.adamw_step(th, np.zeros(3), np.zeros(3), g, 1, lr, 0.9, 0.999, 1e-12, 0.05)
+    np.testing.assert_allclose(th, th0 - lr * (np.sign(g) + 0.05 * th0), rtol=1e-7)
+
+
+def test_adamw_zero_gradient_no_decay_is_identity():
+    th = rnd(5)
+    th0 = th.copy()
+    O.adamw_step(th, np.zeros(5), np.zeros(5), np.zeros(5), 3, 1e-3, 0.9, 0.95, 1e-8, 0.0)
+    np.testing.assert_array_equal(th, th0)
+
+
+@pytest.mark.parametrize("wd", [0.0, 0.1])
+def test_adamw_trajectory_matches_torch_adamw(wd):
+    lr, b1, b2, eps = 4e-4, 0.9, 0.95, 1e-8
+    n, T = 17, 25
+    th0 = rnd(n, scale=0.02)
+    p = torch.nn.Parameter(torch.tensor(th0, dtype=torch.float64))
+    opt = torch.optim.AdamW([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+    th, m1, m2 = th0.copy(), np.zeros(n), np.zeros(n)
+    for t in range(1, T + 1):
+        g = rnd(n, scale=1e-2)
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        O.adamw_step(th, m1, m2, g, t, lr, b1, b2, eps, wd)
+        np.testing.assert_allclose(th, p.detach().numpy(), rtol=1e-11, atol=1e-16)
+    st = opt.state[p]
+    np.testing.assert_allclose(m1, st["exp_avg"].numpy(), rtol=1e-12)
+    np.testing.assert_allclose(m2, st["exp_avg_sq"].numpy(), rtol=1e-12)
+
+
+# -------------------------------------------------------------- Nesterov ---
+def test_nesterov_constant_gradient_closed_form():
+    eta, mu = 0.7, 0.9
+    G = np.array([0.3, -1.5])
+    a0 = np.array([1.0, 2.0])
+    a, u = a0.copy(), np.zeros(2)
+    for k in range(1, 30):
+        O.nesterov_step(a, u, G, eta, mu, True)
+        uk = G * (1 - mu ** k) / (1 - mu)
+        # sum_{j<=k} (G + mu u_j) = G [k + mu/(1-mu) (k - mu (1 - mu^k)/(1-mu))]
+        ak = a0 - eta * G * (k + mu / (1 - mu) * (k - mu * (1 - mu ** k) / (1 - mu)))
+        np.testing.assert_allclose(u, uk, rtol=1e-12)
+        np.testing.assert_allclose(a, ak, rtol=1e-12)
+
+
+def test_zero_momentum_is_plain_sgd():
+    for nesterov in (True, False):
+        a, u = np.array([1.0, -2.0]), np.array([0.0, 0.0])
+        G = np.array([0.5, 0.25])
+        O.nesterov_step(a, u, G, 0.4, 0.0, nesterov)
+        np.testing.assert_allclose(a, [1.0 - 0.2, -2.0 - 0.1], rtol=1e-15)
+
+
+@pytest.mark.parametrize("nesterov", [True, False])
+def test_outer_optimizer_matches_torch_sgd(nesterov):
+    eta, mu, n = 0.7, 0.9, 11
+    a0 = rnd(n)
+    p = torch.nn.Parameter(torch.tensor(a0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=eta, momentum=mu, nesterov=nesterov)
+    a, u = a0.copy(), np.zeros(n)
+    for _ in range(12):
+        G = rnd(n, scale=1e-3)
+        p.grad = torch.tensor(G, dtype=torch.float64)
+        opt.step()
+        O.nesterov_step(a, u, G, eta, mu, nesterov)
+        np.testing.assert_allclose(a, p.detach().numpy(), rtol=1e-12, atol=1e-16)
+
+
+def test_velocity_form_equals_lookahead_form_for_constant_lr():
+    # Sutskever et al. form with w = -eta u: w <- mu w - eta G ; a <- a + mu w - eta G
+    eta, mu, n = 0.4, 0.9, 6
+    a, u = rnd(n), np.zeros(n)
+    a2, w = a.copy(), np.zeros(n)
+    for _ in range(9):
+        G = rnd(n)
+        O.nesterov_step(a, u, G, eta, mu, True)
+        w = mu * w - eta * G
+        a2 = a2 + mu * w - eta * G
+        np.testing.assert_allclose(a, a2, rtol=1e-11, atol=1e-13)
+
+
+# ------------------------------------------------- Algorithm 1 (standard) ---
+def test_standard_momentum_off_lr_one_gives_replica_average():
+    M, n = 5, 9
+    a, u = rnd(n), rnd(n)     # any stale velocity is wiped by mu = 0
+    theta = rnd(M, n)
+    want = theta.mean(axis=0)
+    O.outer_standard(theta, a, u, 1.0, 0.0, True)
+    np.testing.assert_allclose(a, want, rtol=1e-13, atol=1e-15)
+    for m in range(M):
+        np.testing.assert_array_equal(theta[m], a)
+
+
+def test_standard_trajectory_matches_torch_sgd_on_outer_params():
+    # outer gradient written as a - mean_m(theta_m): same real number, other route
+    M, n, eta, mu = 3, 8, 0.7, 0.9
+    a0 = rnd(n, scale=0.02)
+    p = torch.nn.Parameter(torch.tensor(a0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=eta, momentum=mu, nesterov=True)
+    a, u = a0.copy(), np.zeros(n)
+    theta = np.tile(a, (M, 1))
+    for _ in range(7):
+        theta += rnd(M, n, scale=1e-3)             # stands in for the inner phase
+        p.grad = p.detach() - torch.tensor(theta.mean(axis=0))
+        ret = O.outer_standard(theta, a, u, eta, mu, True)
+        np.testing.assert_allclose(ret, p.grad.numpy(), rtol=1e-9, atol=1e-15)
+        opt.step()
+        np.testing.assert_allclose(a, p.detach().numpy(), rtol=1e-11, atol=1e-15)
+        np.testing.assert_array_equal(theta, np.tile(a, (M, 1)))
+
+
+# ---------------------------------------------------- Algorithm 3 (eager) ---
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8])
+def test_eager_combination_equals_mean_of_fresh_local_and_stale_others(M):
+    n = 7
+    delta = rnd(M, n)
+    P = rnd(M, n)
+    D = P.mean(axis=0)          # what the all-reduce of the previous phase delivered
+    G = O.eager_combination(delta, P, D)
+    for m in range(M):
+        others = sum(P[k] for k in range(M) if k != m) if M > 1 else 0.0
+        np.testing.assert_allclose(G[m], (delta[m] + others) / M, rtol=1e-12, atol=1e-14)
+    # mean over replicas: fresh mean / M + (1 - 1/M) stale mean
+    np.testing.assert_allclose(G.mean(axis=0), delta.mean(axis=0) / M + (1 - 1 / M) * D,
+                               rtol=1e-12, atol=1e-14)
+
+
+def test_eager_with_stationary_outer_gradients_feeds_the_stale_mean():
+    M, n = 4, 5
+    P = rnd(M, n)
+    D = rnd(n)
+    G = O.eager_combination(P.copy(), P, D)
+    np.testing.assert_array_equal(G, np.tile(D, (M, 1)))
+
+
+def test_single_replica_eager_call_equals_standard_call():
+    n = 10
+    a1 = rnd(n)
+    u1 = rnd(n, scale=1e-3)
+    th = a1 - rnd(n, scale=1e-3)
+    # standard
+    ths, as_, us = th[None].copy(), a1.copy(), u1.copy()
+    O.outer_standard(ths, as_, us, 0.7, 0.9, True)
+    # eager with M = 1: stored previous mean must be the stored previous local gradient
+    P = rnd(1, n, scale=1e-3)
+    D = P[0].copy()
+    the, ae, ue = th[None].copy(), a1[None].copy(), u1[None].copy()
+    O.outer_eager(the, ae, ue, P, D, 0.7, 0.9, True, apply_update=True)
+    np.testing.assert_allclose(ae[0], as_, rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(ue[0], us, rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(the[0], ths[0], rtol=1e-13, atol=1e-16)
+
+
+@pytest.mark.parametrize("stationary", [False, True])
+def test_identical_replicas_stay_identical_and_local_gradient_is_the_mean(stationary):
+    """Equal replicas: Delta_m equals the mean, every replica makes the same step, and the
+    gradient it feeds OuterOpt is (Delta + (M-1) stale) / M, which is the standard step
+    when the outer gradient did not change since the previous phase."""
+    M, n, eta, mu = 4, 6, 0.7, 0.9
+    a0 = rnd(n)
+    th_row = a0 - rnd(n, scale=1e-3)
+    Prow = (a0 - th_row) if stationary else rnd(n, scale=1e-3)
+    urow = rnd(n, scale=1e-3)
+    theta = np.tile(th_row, (M, 1))
+    a, u, P = np.tile(a0, (M, 1)), np.tile(urow, (M, 1)), np.tile(Prow, (M, 1))
+    D = Prow.copy()
+    O.outer_eager(theta, a, u, P, D, eta, mu, True, True)
+    p = torch.nn.Parameter(torch.tensor(a0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=eta, momentum=mu, nesterov=True)
+    opt.state[p]["momentum_buffer"] = torch.tensor(urow, dtype=torch.float64)
+    p.grad = torch.tensor(((a0 - th_row) + (M - 1) * Prow) / M)
+    opt.step()
+    for m in range(M):
+        np.testing.assert_allclose(a[m], p.detach().numpy(), rtol=1e-12, atol=1e-16)
+        np.testing.assert_array_equal(a[m], a[0])
+        np.testing.assert_array_equal(theta[m], a[m])
+        np.testing.assert_allclose(P[m], D, rtol=1e-13)       # Delta_m is the mean
+    np.testing.assert_allclose(D, a0 - th_row, rtol=1e-12)
+    if stationary:
+        ths, as_, us = np.tile(th_row, (M, 1)), a0.copy(), urow.copy()
+        O.outer_standard(ths, as_, us, eta, mu, True)
+        np.testing.assert_allclose(a[0], as_, rtol=1e-12, atol=1e-16)
+        np.testing.assert_allclose(u[0], us, rtol=1e-12, atol=1e-16)
+
+
+def _torch_replicas(a0, M, eta, mu):
+    ps = [torch.nn.Parameter(torch.tensor(a0, dtype=torch.float64)) for _ in range(M)]
+    return ps, [torch.optim.SGD([p], lr=eta, momentum=mu, nesterov=True) for p in ps]
+
+
+@pytest.mark.parametrize("variant", ["eager", "delayed"])
+def test_multi_phase_trajectory_by_brute_force(variant):
+    """Element-by-element Python re-computation of Algorithms 2 and 3 over several phases:
+    per-replica torch SGD instances as OuterOpt, Python lists as the message in flight,
+    and the paper's second form of the eager gradient."""
+    M, n, eta, mu, phases = 3, 4, 0.7, 0.9, 5
+    a0 = rnd(n, scale=0.02)
+    ps, opts = _torch_replicas(a0, M, eta, mu)
+    theta = np.tile(a0, (M, 1))
+    a, u, P, D = np.tile(a0, (M, 1)), np.zeros((M, n)), np.zeros((M, n)), np.zeros(n)
+    prev_locals = None          # Delta_m^(t-H) as each replica remembers it
+    live = [a0.copy() for _ in range(M)]
+    anchors = [a0.copy() for _ in range(M)]
+    for k in range(1, phases + 1):
+        drift = rnd(M, n, scale=1e-3)
+        theta += drift
+        for m in range(M):
+            live[m] = live[m] + drift[m]
+        # ---- brute force
+        locals_now = [[anchors[m][i] - live[m][i] for i in range(n)] for m in range(M)]
+        if k > 1:
+            for m in range(M):
+                g = []
+                for i in range(n):
+                    stale_mean = sum(prev_locals[q][i] for q in range(M)) / M
+                    if variant == "eager":
+                        g.append((locals_now[m][i]
+                                  + sum(prev_locals[q][i] for q in range(M) if q != m)) / M)
+                    else:
+                        g.append(stale_mean)
+                ps[m].grad = torch.tensor(g, dtype=torch.float64)
+                opts[m].step()
+                anchors[m] = ps[m].detach().numpy().copy()
+        else:
+            # t = H: no outer step; the replica carries on from where it is
+            for m in range(M):
+                anchors[m] = live[m].copy()
+                with torch.no_grad():
+                    ps[m].copy_(torch.tensor(live[m]))
+        for m in range(M):
+            live[m] = anchors[m].copy()
+        prev_locals = locals_now
+        # ---- checker
+        fn = O.outer_eager if variant == "eager" else O.outer_delayed
+        fn(theta, a, u, P, D, eta, mu, True, apply_update=(k > 1))
+        for m in range(M):
+            np.testing.assert_allclose(a[m], anchors[m], rtol=1e-10, atol=1e-15)
+            np.testing.assert_allclose(theta[m], live[m], rtol=1e-10, atol=1e-15)
+            np.testing.assert_allclose(P[m], locals_now[m], rtol=1e-10, atol=1e-15)
+        np.testing.assert_allclose(D, np.mean(np.array(locals_now), axis=0), rtol=1e-10,
+                                   atol=1e-15)
+    # replicas really did diverge under eager updates (Section 2.2, first remark)
+    if variant == "eager":
+        assert np.max(np.abs(a[0] - a[1])) > 0
+
+
+def test_delayed_is_nesterov_on_the_shifted_mean_sequence():
+    M, n, eta, mu = 2, 5, 0.7, 0.9
+    a0 = rnd(n, scale=0.02)
+    theta = np.tile(a0, (M, 1))
+    a, u, P, D = np.tile(a0, (M, 1)), np.zeros((M, n)), np.zeros((M, n)), np.zeros(n)
+    means = []
+    applied = []
+    for k in range(1, 7):
+        theta += rnd(M, n, scale=1e-3)
+        means.append((a - theta).mean(axis=0))
+        a_before = a.copy()
+        O.outer_delayed(theta, a, u, P, D, eta, mu, True, apply_update=(k > 1))
+        if k > 1:
+            applied.append(means[k - 2])
+            # replay a hand-rolled optimizer on worker 0 over the shifted sequence
+            # one step with the right velocity: rebuild it from the applied history
+            vel = np.zeros(n)
+            for G in applied[:-1]:
+                vel = mu * vel + G
+            vel_new = mu * vel + applied[-1]
+            want = a_before[0] - eta * (applied[-1] + mu * vel_new)
+            np.testing.assert_allclose(a[0], want, rtol=1e-11, atol=1e-15)
+        np.testing.assert_allclose(D, means[-1], rtol=1e-12, atol=1e-16)
+
+
+def test_first_boundary_applies_no_outer_step():
+    M, n = 3, 4
+    a0 = rnd(n)
+    theta = np.tile(a0, (M, 1)) + rnd(M, n, scale=1e-3)
+    th_before = theta.copy()
+    for fn in (O.outer_eager, O.outer_delayed):
+        th = theta.copy()
+        a, u, P, D = np.tile(a0, (M, 1)), np.zeros((M, n)), rnd(M, n), rnd(n)
+        fn(th, a, u, P, D, 0.7, 0.9, True, apply_update=False)
+        np.testing.assert_array_equal(th, th_before)      # replicas untouched
+        np.testing.assert_array_equal(a, th_before)       # and they are the next anchors
+        np.testing.assert_array_equal(u, 0.0)
+        np.testing.assert_allclose(P, a0 - th_before, rtol=1e-13)
+        np.testing.assert_allclose(D, (a0 - th_before).mean(axis=0), rtol=1e-12, atol=1e-16)
+
+
+def test_reset_is_idempotent_and_broadcasts():
+    theta = rnd(3, 5)
+    a = rnd(5)
+    O.reset(theta, a)
+    O.reset(theta, a)
+    np.testing.assert_array_equal(theta, np.tile(a, (3, 1)))
+
+
+# -------------------------------------------------- noise and quadratic ---
+def test_mix64_matches_published_splitmix64_outputs(golden_dir):
+    with open(os.path.join(golden_dir, "splitmix64_seed0.txt")) as f:
+        want = [int(l, 16) for l in f if l.strip() and not l.startswith("#")]
+    golden = 0x9E3779B97F4A7C15
+    got = [int(O.mix64(np.uint64((k * golden) % (1 << 64)))) for k in (1, 2, 3)]
+    assert got == want
+
+
+def test_noise_is_standard_normal_and_streams_are_independent():
+    idx = np.arange(200_000)
+    z = O.standard_normal(123, 7, 2, idx)
+    assert abs(z.mean()) < 0.01 and abs(z.var() - 1.0) < 0.01
+    assert stats.kstest(z, "norm").pvalue > 1e-3
+    assert abs(stats.kurtosis(z)) < 0.05
+    # pairs share the radius: z_2j^2 + z_2j+1^2 = -2 ln u1 ~ Exponential(mean 2)
+    r2 = z[0::2] ** 2 + z[1::2] ** 2
+    assert stats.kstest(r2, "expon", args=(0, 2.0)).pvalue > 1e-3
+    # the angle is uniform
+    ang = np.arctan2(z[1::2], z[0::2])
+    assert stats.kstest((ang + np.pi) / (2 * np.pi), "uniform").pvalue > 1e-3
+    for other in (O.standard_normal(123, 8, 2, idx), O.standard_normal(123, 7, 3, idx),
+                  O.standard_normal(124, 7, 2, idx)):
+        assert abs(np.corrcoef(z, other)[0, 1]) < 0.01
+    # a pure function of the coordinates: any slice can be regenerated on its own
+    np.testing.assert_array_equal(O.standard_normal(123, 7, 2, idx[1001:1500]), z[1001:1500])
+    # serial correlation
+    assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 0.01
+
+
+def test_quadratic_gradient_and_loss_fixed_points():
+    n = 33
+    h = np.exp(RNG.uniform(np.log(1e-3), 0.0, n))
+    star = rnd(n)
+    assert O.quadratic_loss(star, h, star) == 0.0
+    g = O.quadratic_gradient(star.copy(), h, star, 0.0, 1, 1, 0)
+    np.testing.assert_array_equal(g, 0.0)
+    # finite-difference check of the gradient against the loss
+    th = rnd(n)
+    g = O.quadratic_gradient(th, h, star, 0.0, 1, 1, 0)
+    for i in (0, 7, 32):
+        e = np.zeros(n)
+        e[i] = 1e-6
+        fd = (O.quadratic_loss(th + e, h, star) - O.quadratic_loss(th - e, h, star)) / 2e-6
+        assert abs(fd - g[i]) < 1e-8 * max(1.0, abs(g[i]))
+    # the noise term is exactly noise_std * z
+    g2 = O.quadratic_gradient(th, h, star, 0.1, 5, 9, 1, index_base=64)
+    z = O.standard_normal(5, 9, 1, 64 + np.arange(n))
+    np.testing.assert_allclose(g2 - g, 0.1 * z, rtol=1e-9, atol=1e-15)
+
+
+@pytest.mark.parametrize("variant", ["standard", "eager", "delayed"])
+def test_noise_free_quadratic_converges(variant):
+    n = 64
+    h = np.exp(RNG.uniform(np.log(1e-3), 0.0, n))
+    star = rnd(n)
+    eta = 0.7 if variant != "delayed" else 0.7 / 4
+    _, losses = O.run_quadratic(variant, M=2, H=20, phases=30, h=h, theta_star=star, seed=3,
+                                noise_std=0.0, lr=2e-2, beta1=0.9, beta2=0.95, eps=1e-8,
+                                weight_decay=0.0, eta=eta, mu=0.5)
+    l0 = O.quadratic_loss(np.zeros(n), h, star)
+    assert losses[-1] < 1e-3 * l0
+    assert np.isfinite(losses).all()
+
+
+def test_quadratic_run_single_replica_standard_matches_torch_optimizers():
+    """Whole driver (inner AdamW x H, outer Nesterov) against torch.optim on one replica."""
+    n, H, phases = 12, 5, 4
+    lr, b1, b2, eps, eta, mu = 1e-2, 0.9, 0.95, 1e-8, 0.7, 0.9
+    h = np.exp(RNG.uniform(np.log(1e-3), 0.0, n))
+    star = rnd(n)
+    st, losses = O.run_quadratic("standard", 1, H, phases, h, star, seed=11, noise_std=0.1,
+                                 lr=lr, beta1=b1, beta2=b2, eps=eps, weight_decay=0.0,
+                                 eta=eta, mu=mu)
+    p = torch.nn.Parameter(torch.zeros(n, dtype=torch.float64))
+    inner = torch.optim.AdamW([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=0.0)
+    outer_p = torch.nn.Parameter(torch.zeros(n, dtype=torch.float64))
+    outer = torch.optim.SGD([outer_p], lr=eta, momentum=mu, nesterov=True)
+    ht, st_t = torch.tensor(h), torch.tensor(star)
+    k = 0
+    for t in range(1, H * phases + 1):
+        z = torch.tensor(O.standard_normal(11, t, 0, np.arange(n)))
+        p.grad = ht * (p.detach() - st_t) + 0.1 * z
+        inner.step()
+        if t % H == 0:
+            outer_p.grad = outer_p.detach() - p.detach()
+            outer.step()
+            with torch.no_grad():
+                p.copy_(outer_p)
+            want = 0.5 * float((ht * (outer_p.detach() - st_t) ** 2).sum())
+            assert abs(losses[k] - want) <= 1e-10 * max(want, 1e-30)
+            k += 1
+    np.testing.assert_allclose(st["a"], outer_p.detach().numpy(), rtol=1e-9, atol=1e-14)
+
+
+def test_eager_run_single_replica_equals_standard_after_first_phase_from_same_state():
+    """M = 1: Delta~_1 = Delta_1, so from equal states one eager call is one standard call,
+    whatever came before (checked inside a noisy quadratic run)."""
+    n, H = 16, 4
+    h = np.exp(RNG.uniform(np.log(1e-3), 0.0, n))
+    star = rnd(n)
+    kw = dict(M=1, H=H, h=h, theta_star=star, seed=5, noise_std=0.1, lr=1e-2, beta1=0.9,
+              beta2=0.95, eps=1e-8, weight_decay=0.0, eta=0.7, mu=0.9)
+    se, _ = O.run_quadratic("eager", phases=3, **kw)
+    # take the eager state, run one more inner phase by hand, then both outer rules
+    theta = se["theta"].copy()
+    m1, m2 = se["m1"].copy(), se["m2"].copy()
+    for t in range(3 * H + 1, 4 * H + 1):
+        O.quadratic_inner_step(theta, m1, m2, h, star, t, 5, 0.1, 1e-2, 0.9, 0.95, 1e-8, 0.0)
+    te, ae, ue, Pe, De = theta.copy(), se["a"].copy(), se["u"].copy(), se["P"].copy(), se["D"].copy()
+    O.outer_eager(te, ae, ue, Pe, De, 0.7, 0.9, True, True)
+    ts, as_, us = theta.copy(), se["a"][0].copy(), se["u"][0].copy()
+    O.outer_standard(ts, as_, us, 0.7, 0.9, True)
+    np.testing.assert_allclose(ae[0], as_, rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(ue[0], us, rtol=1e-12, atol=1e-16)
