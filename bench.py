@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the DiLoCo optimizer sweep on one MI355X.
+
+A step is one pass of the whole hot path over the workload's buffers: one inner AdamW sweep
+of all M replicas, then one fused eager outer step (outer gradients, replica mean, eager
+combination, Nesterov outer update, re-seeding, state rotation).  All buffers are resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload t550m]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+
+def algorithmic_bytes(wl, n):
+    """Bytes the method itself must move per launch (each operand read once, written once)."""
+    M = wl.M
+    ts = 2 if wl.theta_dtype == "bf16" else 4
+    # eager outer: theta (ts) + anchor, vel, prev_local (4 each) per replica, prev_mean once; read + write
+    outer = 2 * (M * (ts + 12) + 4) * n
+    # AdamW: read theta, m1, m2, grad; write theta, m1, m2 (grad has theta's dtype in these workloads)
+    inner = 7 * ts * M * n
+    return outer, inner
+
+
+def stored_traffic(workload):
+    """HBM bytes per launch of the eager kernel from the committed rocprofv3 counter summary."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get("outer_eager_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(wl, sample):
+    """The CPU checker, as it stands, on `sample` parameter indices of the same workload."""
+    import numpy as np
+
+    from oracle import diloco_oracle as O
+    from paper_2502_12996_amd import workloads as W
+    st = {k: W.to_f64(v) for k, v in W.outer_state(wl, sample, seed=99).items()}
+    ad = {k: W.to_f64(v) for k, v in W.adamw_state(wl, sample, seed=99).items()}
+    t0 = time.perf_counter()
+    O.adamw_step(ad["theta"], ad["m1"], ad["m2"], ad["grad"], 31, wl.lr, wl.beta1, wl.beta2, wl.eps,
+                 wl.weight_decay)
+    t1 = time.perf_counter()
+    O.outer_eager(st["theta"], st["anchor"], st["vel"], st["prev_local"], st["prev_mean"],
+                  wl.outer_lr, wl.outer_momentum, True, True)
+    t2 = time.perf_counter()
+    assert np.isfinite(st["anchor"]).all()
+    return dict(value=sample / (t2 - t0), unit="params/s", cores=1, kind="oracle",
+                sample=f"{sample} parameter indices x M={wl.M} replicas of {wl.name}: one AdamW sweep "
+                       f"({t1 - t0:.2f} s) + one eager outer step ({t2 - t1:.2f} s), float64 NumPy, 1 thread",
+                inner_s=t1 - t0, outer_s=t2 - t1)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="t550m")
+    ap.add_argument("--block", type=int, default=None, help="threads per workgroup")
+    ap.add_argument("--xcd-remap", type=int, default=None)
+    ap.add_argument("--pad", type=int, default=0, help="extra elements between replica rows")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 24,
+                    help="parameter indices the CPU checker is timed on (0: skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the M replicas are simulated on it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2502_12996_amd as d
+    from paper_2502_12996_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = W.WORKLOADS[args.workload]
+    M, n = wl.M, wl.n
+    stride = n + args.pad
+    if args.block is not None:
+        d.tune("block", args.block)
+    if args.xcd_remap is not None:
+        d.tune("xcd_remap", args.xcd_remap)
+
+    bf16 = wl.theta_dtype == "bf16"
+    st = W.outer_state(wl, n, device=dev, stride=stride)
+    ad = W.adamw_state(wl, n, device=dev, stride=stride,
+                       grad_dtype=torch.bfloat16 if bf16 else torch.float32)
+    theta = st["theta"]                      # the replicas' live parameters serve both kernels
+    m1, m2, grad = ad["m1"], ad["m2"], ad["grad"]
+    del ad["theta"]
+    torch.cuda.empty_cache()
+
+    def step(t, ev=None):
+        if ev:
+            ev[0].record()
+        d.inner_adamw(theta, m1, m2, grad, n=n, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
+                      weight_decay=wl.weight_decay, step=t)
+        if ev:
+            ev[1].record()
+        d.outer_eager(theta, st["anchor"], st["vel"], st["prev_local"], st["prev_mean"], n=n,
+                      outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
+        if ev:
+            ev[2].record()
+
+    for w in range(args.warmup):
+        step(31 + w)
+    torch.cuda.synchronize()
+    # events sit on torch's current stream, the stream the library launches on
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(31 + args.warmup + k, events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    inner_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    outer_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    assert torch.isfinite(st["anchor"][:, :1024]).all()
+
+    # practical ceiling: plain copy with the same access shape
+    src, dst = grad.view(-1)[:n] if not bf16 else st["vel"].view(-1)[:n], st["prev_local"].view(-1)[:n]
+    cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(3):
+        d.sim_stream_copy(dst, src)
+    cp[0].record()
+    for _ in range(10):
+        d.sim_stream_copy(dst, src)
+    cp[1].record()
+    torch.cuda.synchronize()
+    copy_gbps = 10 * 8 * n / (cp[0].elapsed_time(cp[1]) * 1e-3) / 1e9
+
+    outer_bytes, inner_bytes = algorithmic_bytes(wl, n)
+    outer_gbps = outer_bytes / (outer_ms * 1e-3) / 1e9
+    inner_gbps = inner_bytes / (inner_ms * 1e-3) / 1e9
+    result = {
+        "metric": "outer-step params/sec and achieved HBM GB/s (% of peak) at M workers",
+        "value": n / (ms_step * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if not bf16 else "f32 math, bf16 replica storage",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: M={M} replicas x N={n} params, one AdamW sweep + one "
+                               f"fused eager outer step per step",
+                   "M": M, "N": n, "theta_dtype": wl.theta_dtype, "stride_pad": args.pad,
+                   "block": d.tune_get("block"), "xcd_remap": d.tune_get("xcd_remap")},
+        "outer_step": {"ms": outer_ms, "params_per_s": n / (outer_ms * 1e-3),
+                       "worker_params_per_s": M * n / (outer_ms * 1e-3), "GBps": outer_gbps,
+                       "frac_of_peak": outer_gbps / HBM_PEAK_GBPS},
+        "inner_step": {"ms": inner_ms, "worker_params_per_s": M * n / (inner_ms * 1e-3),
+                       "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS},
+        "copy_ceiling_GBps": copy_gbps,
+        "roofline": {"bound": "hbm", "kernel": "outer_eager_reg_kernel" , "achieved": outer_gbps,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": outer_gbps / HBM_PEAK_GBPS,
+                     "frac_of_copy": outer_gbps / copy_gbps,
+                     "traffic": stored_traffic(wl.name)},
+    }
+    del st, ad, theta, m1, m2, grad, src, dst
+    torch.cuda.empty_cache()
+    if args.cpu_sample > 0:
+        result["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,138 @@
+/*
+ * diloco.h - C ABI of the DiLoCo optimizer sweep for one AMD MI355X (gfx950).
+ *
+ * The library runs, on flat parameter buffers of M simulated replicas that
+ * all live in one GPU's memory, the per-parameter work of DiLoCo with
+ * overlapped communication ("Eager Updates For Overlapped Communication and
+ * Computation in DiLoCo", arXiv 2502.12996):
+ *
+ *   diloco_inner_adamw   line 5 of Algorithms 1-3 (InnerOpt = AdamW) for all replicas
+ *   diloco_outer_sync    Algorithm 1, lines 7-10 (standard DiLoCo outer step)
+ *   diloco_outer_eager   Algorithm 3, lines 7-12 (eager updates) and
+ *                        Algorithm 2, lines 7-11 (naive delayed outer gradients)
+ *   diloco_reset         the assignment theta_m <- outer parameters on its own
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer into memory owned by the caller.  The
+ *     library allocates nothing, frees nothing and keeps no pointer after the
+ *     call returns.  The caller keeps the buffers alive until `stream` has
+ *     passed the call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued asynchronously; the library never synchronises.
+ *   - Buffers with a replica axis are laid out [M][stride]: replica m starts at
+ *     base + m*stride elements and holds n <= stride meaningful elements.
+ *     Sizes and strides count ELEMENTS.  Any (base + offset, n) window of a
+ *     larger buffer is a valid argument, so a caller can sweep fragments of a
+ *     model on different schedules.
+ *   - Arithmetic is fp32 (bf16 buffers are widened exactly on load and rounded
+ *     to nearest-even on store).  The mean over replicas is accumulated in fp64
+ *     in the fixed order m = 0, 1, ..., M-1 and rounded once to fp32.
+ *   - Arguments are validated before anything is launched: a call that returns
+ *     an error has had no effect.  n == 0 is a successful no-op.
+ *   - Pointers must be aligned to their element size.  128-bit accesses are
+ *     used when every pointer is 16-byte aligned (8-byte for bf16) and every
+ *     stride is a multiple of 4 elements; otherwise an element-wise path runs.
+ *   - Return value: DILOCO_OK (0) or one of the diloco_status codes below.
+ */
+#ifndef DILOCO_H
+#define DILOCO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DILOCO_F32 = 0, DILOCO_BF16 = 1 } diloco_dtype;
+
+/* Which outer gradient OuterOpt is fed (diloco_outer_eager). */
+typedef enum {
+    DILOCO_EAGER = 0,   /* Algorithm 3 line 11: (Delta_m - Delta_m_prev)/M + Delta_prev */
+    DILOCO_DELAYED = 1  /* Algorithm 2 line 11: Delta_prev                              */
+} diloco_variant;
+
+typedef enum {
+    DILOCO_OK = 0,
+    DILOCO_ERR_NULL = 1,   /* a required pointer is NULL                                   */
+    DILOCO_ERR_SHAPE = 2,  /* M < 1, M > DILOCO_MAX_REPLICAS, n < 0, stride < n, overflow  */
+    DILOCO_ERR_ALIGN = 3,  /* a pointer is not aligned to its element size                 */
+    DILOCO_ERR_DTYPE = 4,  /* unknown dtype / variant code                                 */
+    DILOCO_ERR_HYPER = 5,  /* non-finite scalar, beta or momentum outside [0,1), eps <= 0,
+                              step < 1, negative weight decay                              */
+    DILOCO_ERR_ALIAS = 6,  /* two buffers the call writes (or reads and writes) overlap    */
+    DILOCO_ERR_LAUNCH = 7  /* the HIP runtime refused the launch                           */
+} diloco_status;
+
+#define DILOCO_MAX_REPLICAS 65535
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* diloco_strerror(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int diloco_version(void);
+
+/*
+ * InnerOpt (Algorithms 1-3, line 5): one AdamW step on every replica.
+ *   m1 <- beta1 m1 + (1-beta1) g ;  m2 <- beta2 m2 + (1-beta2) g^2
+ *   theta <- theta - lr * ( (m1/(1-beta1^step)) / (sqrt(m2/(1-beta2^step)) + eps)
+ *                           + weight_decay * theta )
+ * theta, m1, m2: [M][stride] of param_dtype, updated in place.  grad: [M][stride]
+ * of grad_dtype, read only.  step >= 1 is the caller's global step count t (it keeps
+ * running across outer steps).  The bias corrections are evaluated on the host in
+ * fp64.  Errors: NULL, SHAPE, ALIGN, DTYPE, HYPER, ALIAS, LAUNCH.
+ */
+int diloco_inner_adamw(void* theta, void* m1, void* m2, const void* grad,
+                       int M, int64_t n, int64_t stride,
+                       diloco_dtype param_dtype, diloco_dtype grad_dtype,
+                       double lr, double beta1, double beta2, double eps,
+                       double weight_decay, int64_t step, void* stream);
+
+/*
+ * Standard DiLoCo outer step (Algorithm 1, lines 7-10), fused into one pass:
+ *   Delta_m = anchor - theta_m ; Delta = (1/M) sum_m Delta_m
+ *   vel <- mu vel + Delta ; anchor <- anchor - lr (Delta + mu vel)     (nesterov != 0)
+ *                           anchor <- anchor - lr vel                  (nesterov == 0)
+ *   theta_m <- anchor  for every m
+ * theta: [M][stride] of theta_dtype, overwritten.  anchor, vel: [n] fp32 shared by all
+ * replicas (the outer parameters theta^(t-H) and OuterOpt's velocity), updated in
+ * place.  mean_out: optional [n] fp32 that receives Delta, may be NULL.
+ */
+int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                      float* anchor, float* vel, float* mean_out,
+                      double outer_lr, double outer_momentum, int nesterov, void* stream);
+
+/*
+ * Eager (Algorithm 3, lines 7-12) or naive delayed (Algorithm 2, lines 7-11) outer
+ * step, fused into one read-modify-write pass.  Every replica owns its outer
+ * parameters and its OuterOpt state (Section 2.2: the replicas are never
+ * re-synchronised):
+ *   Delta_m = anchor_m - theta_m ; Delta = (1/M) sum_m Delta_m
+ *   G_m = (Delta_m - prev_local_m)/M + prev_mean     (DILOCO_EAGER)
+ *   G_m = prev_mean                                  (DILOCO_DELAYED)
+ *   vel_m <- mu vel_m + G_m ; anchor_m <- anchor_m - lr (G_m + mu vel_m)  [Nesterov]
+ *   theta_m <- anchor_m ; prev_local_m <- Delta_m ; prev_mean <- Delta
+ * apply_update == 0 is the first boundary t = H, where the listings apply no outer
+ * step: anchor_m <- theta_m, prev_local_m <- Delta_m, prev_mean <- Delta, and theta,
+ * vel stay as they are.
+ * theta: [M][stride] of theta_dtype.  anchor, vel, prev_local: [M][state_stride] fp32.
+ * prev_mean: [n] fp32.  All are read and written (vel and prev_local are not read when
+ * apply_update == 0; prev_local is not read for DILOCO_DELAYED).
+ */
+int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                       float* anchor, float* vel, float* prev_local, int64_t state_stride,
+                       float* prev_mean,
+                       double outer_lr, double outer_momentum, int nesterov,
+                       diloco_variant variant, int apply_update, void* stream);
+
+/*
+ * theta_m <- anchor_m for every replica (the left-hand side of Algorithm 1 line 10 /
+ * Algorithm 3 line 12 on its own).  anchor_stride == 0 broadcasts one shared [n]
+ * buffer; otherwise anchor is [M][anchor_stride].  Idempotent.
+ */
+int diloco_reset(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                 const float* anchor, int64_t anchor_stride, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DILOCO_H */

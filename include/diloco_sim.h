@@ -1,0 +1,75 @@
+/*
+ * diloco_sim.h - harness entry points: the noisy quadratic stand-in problem and
+ * launch tuning.  Same conventions as diloco.h (device pointers owned by the
+ * caller, element strides, asynchronous on `stream`, validation before launch).
+ *
+ * The paper's workers run forward/backward passes of a language model (lines 3-4
+ * of Algorithms 1-3); here a separable quadratic
+ *     L(theta) = 0.5 * sum_i h_i (theta_i - theta*_i)^2
+ * stands in for it, and each replica's gradient is made inside the kernel:
+ *     g_m[i] = h_i (theta_m[i] - theta*_i) + noise_std * z(seed, step, m, i)
+ * z is a counter-based standard normal: elements 2j and 2j+1 of replica m at
+ * step t share the 64-bit word x = mix64(key + (j+1)*0x9E3779B97F4A7C15), where
+ * mix64 is the splitmix64 output function (Steele, Lea, Flood 2014) and
+ * key = mix64(mix64(seed + (t+1)*G) + (m+1)*G), G the same odd constant;
+ * u1 = ((x >> 40) + 1) / 2^24, u2 = ((x >> 16) & 0xFFFFFF) / 2^24,
+ * r = sqrt(-2 ln u1), z_2j = r cos(2 pi u2), z_2j+1 = r sin(2 pi u2).
+ */
+#ifndef DILOCO_SIM_H
+#define DILOCO_SIM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Lines 3-5 of Algorithms 1-3 on the quadratic: gradient made in registers, then the
+ * AdamW step of diloco_inner_adamw, for every replica.  theta, m1, m2: [M][stride]
+ * fp32 in place.  h, theta_star: [n] fp32 shared.  index_base is the global index of
+ * element 0 of this window (so windows of one buffer draw the noise of their own
+ * elements); it must be a multiple of 4.  step >= 1.
+ */
+int diloco_sim_quadratic_inner(float* theta, float* m1, float* m2,
+                               int M, int64_t n, int64_t stride,
+                               const float* h, const float* theta_star,
+                               double noise_std, uint64_t seed, int64_t index_base,
+                               double lr, double beta1, double beta2, double eps,
+                               double weight_decay, int64_t step, void* stream);
+
+/* Number of fp64 partial sums diloco_sim_quadratic_loss needs for n elements. */
+int64_t diloco_sim_loss_workspace(int64_t n);
+
+/*
+ * loss_out[0] <- 0.5 * sum_i h_i (tbar_i - theta*_i)^2 with tbar = (1/M) sum_m theta_m
+ * (fp64 accumulation, fixed order: deterministic).  theta: [M][stride] fp32.
+ * partials: device workspace of n_partials >= diloco_sim_loss_workspace(n) doubles,
+ * overwritten.  loss_out: one device double.
+ */
+int diloco_sim_quadratic_loss(const float* theta, int M, int64_t n, int64_t stride,
+                              const float* h, const float* theta_star,
+                              double* partials, int64_t n_partials, double* loss_out,
+                              void* stream);
+
+/*
+ * Measurement aid: dst[i] <- src[i] for n fp32 elements with the same 128-bit
+ * non-temporal accesses and launch shape as the sweep kernels (moves 8n bytes).  The
+ * rate it reaches is the practical HBM ceiling the sweeps are compared with.
+ * dst, src: 16-byte aligned, non-overlapping.
+ */
+int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream);
+
+/*
+ * Launch tuning for measurements.  Keys: "block" (threads per workgroup: 64..512,
+ * power of two), "xcd_remap" (0/1: give each of the 8 XCDs a contiguous slice of the
+ * index space).
+ * Returns DILOCO_OK or DILOCO_ERR_HYPER for an unknown key / value.  Not thread safe.
+ */
+int diloco_tune(const char* key, int value);
+int diloco_tune_get(const char* key);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DILOCO_SIM_H */

@@ -1,0 +1,10 @@
+"""MI355X-native optimizer sweep of DiLoCo with eager outer updates (arXiv 2502.12996).
+
+`binding` wraps the C-ABI library (HIP kernels for gfx950), `workloads` holds the
+synthetic benchmark configurations and seeded input generators, `build` compiles the
+library in-tree.  The shared library is loaded on first use and there is no fallback.
+"""
+from . import binding, workloads  # noqa: F401
+from .binding import (BF16, DELAYED, EAGER, F32, DilocoError, inner_adamw, outer_eager,  # noqa: F401
+                      outer_sync, reset, sim_loss_workspace, sim_quadratic_inner,
+                      sim_quadratic_loss, sim_stream_copy, strerror, tune, tune_get, version)

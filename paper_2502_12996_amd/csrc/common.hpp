@@ -1,0 +1,135 @@
+// Shared device helpers and host-side argument checks for the DiLoCo sweep kernels (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <cmath>
+
+#include "diloco.h"
+
+namespace diloco {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxBlock = 512;  // largest workgroup the streaming kernels are launched with
+constexpr int kXcds = 8;  // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+
+// ---------------------------------------------------------------- memory access
+// Every byte of this path is touched once per call, so loads and stores carry the
+// non-temporal hint: nothing is worth keeping in L2.
+template <typename T> struct Vec4;
+template <> struct Vec4<float> { using type = f4; };
+template <> struct Vec4<__bf16> { using type = bf4; };
+
+template <typename T>
+__device__ __forceinline__ f4 load4(const T* p) {
+    using V = typename Vec4<T>::type;
+    V v = __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+    return __builtin_convertvector(v, f4);  // bf16 -> fp32 is exact
+}
+template <typename T>
+__device__ __forceinline__ void store4(T* p, f4 x) {
+    using V = typename Vec4<T>::type;
+    V v = __builtin_convertvector(x, V);  // fp32 -> bf16 rounds to nearest even
+    __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
+}
+template <typename T>
+__device__ __forceinline__ float load1(const T* p) {
+    return static_cast<float>(__builtin_nontemporal_load(p));
+}
+template <typename T>
+__device__ __forceinline__ void store1(T* p, float x) {
+    __builtin_nontemporal_store(static_cast<T>(x), p);
+}
+
+// ---------------------------------------------------------------- fp32 math on 1 or 4 lanes
+__device__ __forceinline__ float fma_(float a, float b, float c) { return fmaf(a, b, c); }
+__device__ __forceinline__ f4 fma_(f4 a, f4 b, f4 c) { return __builtin_elementwise_fma(a, b, c); }
+__device__ __forceinline__ float sqrt_(float x) { return sqrtf(x); }
+__device__ __forceinline__ f4 sqrt_(f4 x) { return f4{sqrtf(x.x), sqrtf(x.y), sqrtf(x.z), sqrtf(x.w)}; }
+template <typename T> __device__ __forceinline__ T splat(float x);
+template <> __device__ __forceinline__ float splat<float>(float x) { return x; }
+template <> __device__ __forceinline__ f4 splat<f4>(float x) { return f4{x, x, x, x}; }
+
+// Logical workgroup index.  per_xcd == 0: identity.  Otherwise the grid holds 8*per_xcd
+// workgroups and die k (hardware id % 8) walks the contiguous slice [k*per_xcd, (k+1)*per_xcd).
+__device__ __forceinline__ int64_t logical_block(int64_t per_xcd) {
+    int64_t b = blockIdx.x;
+    if (per_xcd == 0) return b;
+    return (b % kXcds) * per_xcd + b / kXcds;
+}
+
+// ---------------------------------------------------------------- host side
+struct Tuning {
+    int block = 256;
+    int xcd_remap = 0;
+};
+Tuning& tuning();
+
+struct Range {
+    const void* p;
+    int64_t bytes;
+    bool written;
+};
+
+inline bool is_finite(double x) { return std::isfinite(x); }
+inline bool in_unit(double x) { return std::isfinite(x) && x >= 0.0 && x < 1.0; }
+inline int elem_size(int dtype) { return dtype == DILOCO_F32 ? 4 : 2; }
+inline bool valid_dtype(int dtype) { return dtype == DILOCO_F32 || dtype == DILOCO_BF16; }
+
+// [M][stride] buffer with n meaningful elements per row: bytes spanned from the base.
+inline int64_t extent_bytes(int M, int64_t n, int64_t stride, int esize) {
+    return ((int64_t)(M - 1) * stride + n) * esize;
+}
+// M, n, stride sanity incl. overflow of the largest element offset.
+inline int check_shape(int M, int64_t n, int64_t stride) {
+    if (M < 1 || M > DILOCO_MAX_REPLICAS || n < 0) return DILOCO_ERR_SHAPE;
+    if (stride < n && M > 1) return DILOCO_ERR_SHAPE;
+    if (stride < 0) return DILOCO_ERR_SHAPE;
+    const int64_t lim = (int64_t)1 << 60;
+    if (n > lim || stride > lim / M) return DILOCO_ERR_SHAPE;
+    return DILOCO_OK;
+}
+inline bool aligned_to(const void* p, int a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline int check_alias(const Range* r, int count) {
+    for (int i = 0; i < count; ++i)
+        for (int j = i + 1; j < count; ++j) {
+            if (!r[i].p || !r[j].p || r[i].bytes == 0 || r[j].bytes == 0) continue;
+            if (!r[i].written && !r[j].written) continue;
+            const char* a0 = static_cast<const char*>(r[i].p);
+            const char* b0 = static_cast<const char*>(r[j].p);
+            if (a0 < b0 + r[j].bytes && b0 < a0 + r[i].bytes) return DILOCO_ERR_ALIAS;
+        }
+    return DILOCO_OK;
+}
+
+// Grid for `threads` work items, `block` threads per workgroup; per_xcd as logical_block wants it.
+struct Grid {
+    unsigned blocks;
+    int64_t per_xcd;
+};
+inline Grid make_grid(int64_t threads, int block) {
+    int64_t nb = (threads + block - 1) / block;
+    Grid g;
+    if (tuning().xcd_remap && nb >= 4 * kXcds) {
+        g.per_xcd = (nb + kXcds - 1) / kXcds;
+        g.blocks = (unsigned)(g.per_xcd * kXcds);
+    } else {
+        g.per_xcd = 0;
+        g.blocks = (unsigned)nb;
+    }
+    return g;
+}
+// 2^31-1 workgroups per grid dimension.
+inline bool grid_fits(int64_t threads, int block) {
+    return (threads + block - 1) / block + kXcds < ((int64_t)1 << 31);
+}
+
+inline int launch_status() {
+    return hipGetLastError() == hipSuccess ? DILOCO_OK : DILOCO_ERR_LAUNCH;
+}
+
+}  // namespace diloco

@@ -1,0 +1,494 @@
+// Outer-step kernels: standard DiLoCo (Algorithm 1, lines 7-10), eager updates
+// (Algorithm 3, lines 7-12), naive delayed outer gradients (Algorithm 2, lines 7-11)
+// and the re-seeding of replicas from their outer parameters.
+//
+// One thread owns 4 consecutive parameters (one 128-bit access per fp32 stream) of ALL
+// replicas, so the cross-replica mean is a register accumulation in the fixed order
+// m = 0..M-1 with no cross-lane traffic.  The whole outer step is one read-modify-write
+// pass: each byte of theta_m, the outer parameters, the velocity, the previous local
+// and previous averaged outer gradient is read once and written once.
+#include "common.hpp"
+
+namespace diloco {
+
+struct OuterScalars {
+    float mu;        // outer momentum
+    float c_g;       // coefficient of G in the parameter step: lr (Nesterov) or 0
+    float c_u;       // coefficient of the new velocity: lr*mu (Nesterov) or lr
+    float inv_M;     // 1/M in fp32 (eager combination)
+    double inv_M_d;  // 1/M in fp64 (mean)
+};
+
+enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
+
+// OuterOpt on one value: u <- mu u + G ; a <- a - (c_g G + c_u u).
+template <typename T>
+__device__ __forceinline__ void outer_opt(T& a, T& u, T G, const OuterScalars& sc) {
+    u = fma_(splat<T>(sc.mu), u, G);
+    a = a - fma_(splat<T>(sc.c_u), u, sc.c_g * G);
+}
+// Algorithm 3 line 11: (Delta_m - Delta_m_prev)/M + Delta_prev.
+template <typename T>
+__device__ __forceinline__ T eager_gradient(T d, T p, T Dold, const OuterScalars& sc) {
+    return fma_(d - p, splat<T>(sc.inv_M), Dold);
+}
+
+// ------------------------------------------------------------------ element-wise path
+// Runtime M, one parameter index, two passes over the replicas (the second re-reads
+// theta_m and anchor_m).  Serves misaligned buffers and the ragged tail of the vector
+// kernels; same arithmetic, same order.
+template <typename TT, int MODE>
+__device__ void eager_element(TT* theta, float* anchor, float* vel, float* P, float* D, int M,
+                              int64_t stride, int64_t sstride, int64_t i, const OuterScalars& sc) {
+    double s = 0.0;
+    for (int m = 0; m < M; ++m) {
+        float a = load1(anchor + m * sstride + i);
+        float th = load1(theta + m * stride + i);
+        s += (double)(a - th);
+    }
+    const float dbar = (float)(s * sc.inv_M_d);
+    const float Dold = (MODE == MODE_RECORD) ? 0.f : load1(D + i);
+    for (int m = 0; m < M; ++m) {
+        float a = load1(anchor + m * sstride + i);
+        float th = load1(theta + m * stride + i);
+        float d = a - th;
+        if (MODE == MODE_RECORD) {
+            store1(anchor + m * sstride + i, th);
+        } else {
+            float u = load1(vel + m * sstride + i);
+            float G = Dold;
+            if (MODE == MODE_EAGER) G = eager_gradient(d, load1(P + m * sstride + i), Dold, sc);
+            outer_opt(a, u, G, sc);
+            store1(theta + m * stride + i, a);
+            store1(anchor + m * sstride + i, a);
+            store1(vel + m * sstride + i, u);
+        }
+        store1(P + m * sstride + i, d);
+    }
+    store1(D + i, dbar);
+}
+
+template <typename TT, int MODE>
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_scalar_kernel(TT* theta, float* anchor, float* vel, float* P, float* D,
+                                          int M, int64_t n, int64_t stride, int64_t sstride,
+                                          OuterScalars sc, int64_t per_xcd) {
+    int64_t i = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    if (i < n) eager_element<TT, MODE>(theta, anchor, vel, P, D, M, stride, sstride, i, sc);
+}
+
+// Tail of a vector kernel: the thread right after the last full vector sweeps n % 4 elements.
+template <typename TT, int MODE>
+__device__ __forceinline__ void eager_tail(TT* theta, float* anchor, float* vel, float* P, float* D,
+                                           int M, int64_t n, int64_t stride, int64_t sstride,
+                                           const OuterScalars& sc) {
+    for (int64_t i = n & ~(int64_t)3; i < n; ++i)
+        eager_element<TT, MODE>(theta, anchor, vel, P, D, M, stride, sstride, i, sc);
+}
+
+// ------------------------------------------------------------------ register path
+// M known at compile time: anchor_m and Delta_m of all replicas stay in registers between
+// the reduction and the update (2*M*4 VGPRs), nothing is read twice.
+template <int M, typename TT, int MODE>
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restrict__ theta, float* __restrict__ anchor,
+                                       float* __restrict__ vel, float* __restrict__ P,
+                                       float* __restrict__ D, int64_t n, int64_t stride,
+                                       int64_t sstride, OuterScalars sc, int64_t per_xcd) {
+    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    const int64_t nvec = n >> 2;
+    if (v >= nvec) {
+        if (v == nvec) eager_tail<TT, MODE>(theta, anchor, vel, P, D, M, n, stride, sstride, sc);
+        return;
+    }
+    const int64_t i = v << 2;
+    f4 a[M], d[M], u[M], p[M];
+    f4 Dold = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        a[m] = load4(anchor + m * sstride + i);
+        d[m] = load4(theta + m * stride + i);  // theta for now
+    }
+    if (MODE != MODE_RECORD) {
+        Dold = load4(D + i);
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            u[m] = load4(vel + m * sstride + i);
+            if (MODE == MODE_EAGER) p[m] = load4(P + m * sstride + i);
+        }
+    }
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    f4 th[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        th[m] = d[m];
+        d[m] = a[m] - th[m];
+        s0 += (double)d[m].x;
+        s1 += (double)d[m].y;
+        s2 += (double)d[m].z;
+        s3 += (double)d[m].w;
+    }
+    f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
+               (float)(s3 * sc.inv_M_d)};
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        if (MODE == MODE_RECORD) {
+            store4(anchor + m * sstride + i, th[m]);
+        } else {
+            f4 G = Dold;
+            if (MODE == MODE_EAGER) G = eager_gradient(d[m], p[m], Dold, sc);
+            f4 an = a[m], un = u[m];
+            outer_opt(an, un, G, sc);
+            store4(theta + m * stride + i, an);
+            store4(anchor + m * sstride + i, an);
+            store4(vel + m * sstride + i, un);
+        }
+        store4(P + m * sstride + i, d[m]);
+    }
+    store4(D + i, dbar);
+}
+
+// ------------------------------------------------------------------ LDS-staged path
+// Any M: anchor_m and Delta_m are parked in LDS (32 bytes per thread and replica) between
+// the two loops.  A thread only reads back what it wrote itself, so no barrier is needed.
+template <typename TT, int MODE>
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restrict__ theta, float* __restrict__ anchor,
+                                       float* __restrict__ vel, float* __restrict__ P,
+                                       float* __restrict__ D, int M, int64_t n, int64_t stride,
+                                       int64_t sstride, OuterScalars sc, int64_t per_xcd) {
+    extern __shared__ f4 stage[];  // [M][2][blockDim.x]
+    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    const int64_t nvec = n >> 2;
+    if (v >= nvec) {
+        if (v == nvec) eager_tail<TT, MODE>(theta, anchor, vel, P, D, M, n, stride, sstride, sc);
+        return;
+    }
+    const int64_t i = v << 2;
+    const int B = blockDim.x, tid = threadIdx.x;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll 4
+    for (int m = 0; m < M; ++m) {
+        f4 a = load4(anchor + m * sstride + i);
+        f4 th = load4(theta + m * stride + i);
+        f4 d = a - th;
+        s0 += (double)d.x;
+        s1 += (double)d.y;
+        s2 += (double)d.z;
+        s3 += (double)d.w;
+        stage[(2 * m) * B + tid] = (MODE == MODE_RECORD) ? th : a;
+        stage[(2 * m + 1) * B + tid] = d;
+    }
+    f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
+               (float)(s3 * sc.inv_M_d)};
+    f4 Dold = {0.f, 0.f, 0.f, 0.f};
+    if (MODE != MODE_RECORD) Dold = load4(D + i);
+#pragma unroll 4
+    for (int m = 0; m < M; ++m) {
+        f4 an = stage[(2 * m) * B + tid];
+        f4 d = stage[(2 * m + 1) * B + tid];
+        if (MODE == MODE_RECORD) {
+            store4(anchor + m * sstride + i, an);  // holds theta_m
+        } else {
+            f4 un = load4(vel + m * sstride + i);
+            f4 G = Dold;
+            if (MODE == MODE_EAGER) G = eager_gradient(d, load4(P + m * sstride + i), Dold, sc);
+            outer_opt(an, un, G, sc);
+            store4(theta + m * stride + i, an);
+            store4(anchor + m * sstride + i, an);
+            store4(vel + m * sstride + i, un);
+        }
+        store4(P + m * sstride + i, d);
+    }
+    store4(D + i, dbar);
+}
+
+// ------------------------------------------------------------------ standard DiLoCo
+// Shared outer parameters: nothing per replica has to survive the reduction, so a runtime
+// loop over m suffices.  VEC = 4 (128-bit) or 1 (element-wise).
+template <typename TT>
+__global__ __launch_bounds__(kMaxBlock) void outer_sync_vec_kernel(TT* __restrict__ theta, float* __restrict__ anchor,
+                                      float* __restrict__ vel, float* __restrict__ mean_out, int M,
+                                      int64_t n, int64_t stride, OuterScalars sc, int64_t per_xcd) {
+    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    const int64_t nvec = n >> 2;
+    if (v > nvec) return;
+    if (v == nvec) {
+        for (int64_t i = n & ~(int64_t)3; i < n; ++i) {
+            float a = load1(anchor + i), u = load1(vel + i);
+            double s = 0.0;
+            for (int m = 0; m < M; ++m) s += (double)(a - load1(theta + m * stride + i));
+            float dbar = (float)(s * sc.inv_M_d);
+            outer_opt(a, u, dbar, sc);
+            for (int m = 0; m < M; ++m) store1(theta + m * stride + i, a);
+            store1(anchor + i, a);
+            store1(vel + i, u);
+            if (mean_out) store1(mean_out + i, dbar);
+        }
+        return;
+    }
+    const int64_t i = v << 2;
+    f4 a = load4(anchor + i), u = load4(vel + i);
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll 8
+    for (int m = 0; m < M; ++m) {
+        f4 d = a - load4(theta + m * stride + i);
+        s0 += (double)d.x;
+        s1 += (double)d.y;
+        s2 += (double)d.z;
+        s3 += (double)d.w;
+    }
+    f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
+               (float)(s3 * sc.inv_M_d)};
+    outer_opt(a, u, dbar, sc);
+#pragma unroll 8
+    for (int m = 0; m < M; ++m) store4(theta + m * stride + i, a);
+    store4(anchor + i, a);
+    store4(vel + i, u);
+    if (mean_out) store4(mean_out + i, dbar);
+}
+
+template <typename TT>
+__global__ __launch_bounds__(kMaxBlock) void outer_sync_scalar_kernel(TT* theta, float* anchor, float* vel, float* mean_out,
+                                         int M, int64_t n, int64_t stride, OuterScalars sc,
+                                         int64_t per_xcd) {
+    const int64_t i = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float a = load1(anchor + i), u = load1(vel + i);
+    double s = 0.0;
+    for (int m = 0; m < M; ++m) s += (double)(a - load1(theta + m * stride + i));
+    float dbar = (float)(s * sc.inv_M_d);
+    outer_opt(a, u, dbar, sc);
+    for (int m = 0; m < M; ++m) store1(theta + m * stride + i, a);
+    store1(anchor + i, a);
+    store1(vel + i, u);
+    if (mean_out) store1(mean_out + i, dbar);
+}
+
+// ------------------------------------------------------------------ reset
+template <typename TT>
+__global__ __launch_bounds__(kMaxBlock) void reset_vec_kernel(TT* __restrict__ theta, const float* __restrict__ anchor,
+                                 int64_t n, int64_t stride, int64_t astride, int64_t per_xcd) {
+    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    const int64_t nvec = n >> 2;
+    const int m = blockIdx.y;
+    if (v > nvec) return;
+    if (v == nvec) {
+        for (int64_t i = n & ~(int64_t)3; i < n; ++i)
+            store1(theta + m * stride + i, load1(anchor + m * astride + i));
+        return;
+    }
+    const int64_t i = v << 2;
+    store4(theta + m * stride + i, load4(anchor + m * astride + i));
+}
+template <typename TT>
+__global__ __launch_bounds__(kMaxBlock) void reset_scalar_kernel(TT* theta, const float* anchor, int64_t n, int64_t stride,
+                                    int64_t astride, int64_t per_xcd) {
+    const int64_t i = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    const int m = blockIdx.y;
+    if (i < n) store1(theta + m * stride + i, load1(anchor + m * astride + i));
+}
+
+// ------------------------------------------------------------------ host dispatch
+static OuterScalars make_scalars(int M, double lr, double mu, int nesterov) {
+    OuterScalars sc;
+    sc.mu = (float)mu;
+    sc.c_g = nesterov ? (float)lr : 0.f;
+    sc.c_u = nesterov ? (float)(lr * mu) : (float)lr;
+    sc.inv_M = (float)(1.0 / M);
+    sc.inv_M_d = 1.0 / M;
+    return sc;
+}
+
+template <typename TT, int MODE>
+static int launch_eager(TT* theta, float* anchor, float* vel, float* P, float* D, int M, int64_t n,
+                        int64_t stride, int64_t sstride, const OuterScalars& sc, bool vec_ok,
+                        hipStream_t st) {
+    const int block = tuning().block;
+    if (!vec_ok) {
+        if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
+        Grid g = make_grid(n, block);
+        hipLaunchKernelGGL((outer_eager_scalar_kernel<TT, MODE>), dim3(g.blocks), dim3(block), 0, st,
+                           theta, anchor, vel, P, D, M, n, stride, sstride, sc, g.per_xcd);
+        return launch_status();
+    }
+    const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
+    if (!grid_fits(threads, 64)) return DILOCO_ERR_SHAPE;
+#define DILOCO_REG_CASE(MM)                                                                       \
+    case MM: {                                                                                    \
+        Grid g = make_grid(threads, block);                                                       \
+        hipLaunchKernelGGL((outer_eager_reg_kernel<MM, TT, MODE>), dim3(g.blocks), dim3(block), 0, \
+                           st, theta, anchor, vel, P, D, n, stride, sstride, sc, g.per_xcd);      \
+        return launch_status();                                                                   \
+    }
+    switch (M) {
+        DILOCO_REG_CASE(1)
+        DILOCO_REG_CASE(2)
+        DILOCO_REG_CASE(3)
+        DILOCO_REG_CASE(4)
+        DILOCO_REG_CASE(8)
+        default: break;
+    }
+#undef DILOCO_REG_CASE
+    // LDS staging: 32 bytes per thread and replica; shrink the workgroup until it fits.
+    int dev = 0, lds_max = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
+        return DILOCO_ERR_LAUNCH;
+    int b = block;
+    while (b > 64 && (int64_t)b * 32 * M > lds_max) b >>= 1;
+    const int64_t lds = (int64_t)b * 32 * M;
+    if (lds <= lds_max) {
+        if (lds > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&outer_eager_lds_kernel<TT, MODE>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return DILOCO_ERR_LAUNCH;
+        Grid g = make_grid(threads, b);
+        hipLaunchKernelGGL((outer_eager_lds_kernel<TT, MODE>), dim3(g.blocks), dim3(b), (size_t)lds,
+                           st, theta, anchor, vel, P, D, M, n, stride, sstride, sc, g.per_xcd);
+        return launch_status();
+    }
+    // M too large even for one wavefront per workgroup: element-wise two-pass kernel.
+    if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
+    Grid g = make_grid(n, block);
+    hipLaunchKernelGGL((outer_eager_scalar_kernel<TT, MODE>), dim3(g.blocks), dim3(block), 0, st,
+                       theta, anchor, vel, P, D, M, n, stride, sstride, sc, g.per_xcd);
+    return launch_status();
+}
+
+template <typename TT>
+static int dispatch_eager(TT* theta, float* anchor, float* vel, float* P, float* D, int M, int64_t n,
+                          int64_t stride, int64_t sstride, const OuterScalars& sc, bool vec_ok,
+                          int mode, hipStream_t st) {
+    switch (mode) {
+        case MODE_RECORD:
+            return launch_eager<TT, MODE_RECORD>(theta, anchor, vel, P, D, M, n, stride, sstride, sc,
+                                                 vec_ok, st);
+        case MODE_EAGER:
+            return launch_eager<TT, MODE_EAGER>(theta, anchor, vel, P, D, M, n, stride, sstride, sc,
+                                                vec_ok, st);
+        default:
+            return launch_eager<TT, MODE_DELAYED>(theta, anchor, vel, P, D, M, n, stride, sstride, sc,
+                                                  vec_ok, st);
+    }
+}
+
+}  // namespace diloco
+
+using namespace diloco;
+
+extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                  int64_t stride, float* anchor, float* vel, float* prev_local,
+                                  int64_t state_stride, float* prev_mean, double outer_lr,
+                                  double outer_momentum, int nesterov, diloco_variant variant,
+                                  int apply_update, void* stream) {
+    if (!theta || !anchor || !vel || !prev_local || !prev_mean) return DILOCO_ERR_NULL;
+    if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
+    if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
+    if (int e = check_shape(M, n, stride)) return e;
+    if (int e = check_shape(M, n, state_stride)) return e;
+    if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
+    const int es = elem_size(theta_dtype);
+    if (!aligned_to(theta, es) || !aligned_to(anchor, 4) || !aligned_to(vel, 4) ||
+        !aligned_to(prev_local, 4) || !aligned_to(prev_mean, 4))
+        return DILOCO_ERR_ALIGN;
+    Range r[5] = {{theta, extent_bytes(M, n, stride, es), true},
+                  {anchor, extent_bytes(M, n, state_stride, 4), true},
+                  {vel, extent_bytes(M, n, state_stride, 4), true},
+                  {prev_local, extent_bytes(M, n, state_stride, 4), true},
+                  {prev_mean, n * 4, true}};
+    if (int e = check_alias(r, 5)) return e;
+    if (n == 0) return DILOCO_OK;
+    const bool vec_ok = aligned_to(theta, 4 * es) && aligned_to(anchor, 16) && aligned_to(vel, 16) &&
+                        aligned_to(prev_local, 16) && aligned_to(prev_mean, 16) &&
+                        (M == 1 || (stride % 4 == 0 && state_stride % 4 == 0));
+    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    const int mode = !apply_update ? MODE_RECORD : (variant == DILOCO_EAGER ? MODE_EAGER : MODE_DELAYED);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (theta_dtype == DILOCO_F32)
+        return dispatch_eager<float>(static_cast<float*>(theta), anchor, vel, prev_local, prev_mean, M,
+                                     n, stride, state_stride, sc, vec_ok, mode, st);
+    return dispatch_eager<__bf16>(static_cast<__bf16*>(theta), anchor, vel, prev_local, prev_mean, M, n,
+                                  stride, state_stride, sc, vec_ok, mode, st);
+}
+
+template <typename TT>
+static int launch_sync(TT* theta, float* anchor, float* vel, float* mean_out, int M, int64_t n,
+                       int64_t stride, const OuterScalars& sc, bool vec_ok, hipStream_t st) {
+    const int block = tuning().block;
+    const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
+    if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
+    Grid g = make_grid(threads, block);
+    if (vec_ok)
+        hipLaunchKernelGGL((outer_sync_vec_kernel<TT>), dim3(g.blocks), dim3(block), 0, st, theta,
+                           anchor, vel, mean_out, M, n, stride, sc, g.per_xcd);
+    else
+        hipLaunchKernelGGL((outer_sync_scalar_kernel<TT>), dim3(g.blocks), dim3(block), 0, st, theta,
+                           anchor, vel, mean_out, M, n, stride, sc, g.per_xcd);
+    return launch_status();
+}
+
+extern "C" int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                 int64_t stride, float* anchor, float* vel, float* mean_out,
+                                 double outer_lr, double outer_momentum, int nesterov,
+                                 void* stream) {
+    if (!theta || !anchor || !vel) return DILOCO_ERR_NULL;
+    if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
+    if (int e = check_shape(M, n, stride)) return e;
+    if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
+    const int es = elem_size(theta_dtype);
+    if (!aligned_to(theta, es) || !aligned_to(anchor, 4) || !aligned_to(vel, 4) ||
+        !aligned_to(mean_out, 4))
+        return DILOCO_ERR_ALIGN;
+    Range r[4] = {{theta, extent_bytes(M, n, stride, es), true},
+                  {anchor, n * 4, true},
+                  {vel, n * 4, true},
+                  {mean_out, n * 4, true}};
+    if (int e = check_alias(r, 4)) return e;
+    if (n == 0) return DILOCO_OK;
+    const bool vec_ok = aligned_to(theta, 4 * es) && aligned_to(anchor, 16) && aligned_to(vel, 16) &&
+                        aligned_to(mean_out, 16) && (M == 1 || stride % 4 == 0);
+    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (theta_dtype == DILOCO_F32)
+        return launch_sync<float>(static_cast<float*>(theta), anchor, vel, mean_out, M, n, stride, sc,
+                                  vec_ok, st);
+    return launch_sync<__bf16>(static_cast<__bf16*>(theta), anchor, vel, mean_out, M, n, stride, sc,
+                               vec_ok, st);
+}
+
+template <typename TT>
+static int launch_reset(TT* theta, const float* anchor, int M, int64_t n, int64_t stride,
+                        int64_t astride, bool vec_ok, hipStream_t st) {
+    const int block = tuning().block;
+    const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
+    if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
+    Grid g = make_grid(threads, block);
+    if (vec_ok)
+        hipLaunchKernelGGL((reset_vec_kernel<TT>), dim3(g.blocks, M), dim3(block), 0, st, theta, anchor,
+                           n, stride, astride, g.per_xcd);
+    else
+        hipLaunchKernelGGL((reset_scalar_kernel<TT>), dim3(g.blocks, M), dim3(block), 0, st, theta,
+                           anchor, n, stride, astride, g.per_xcd);
+    return launch_status();
+}
+
+extern "C" int diloco_reset(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                            const float* anchor, int64_t anchor_stride, void* stream) {
+    if (!theta || !anchor) return DILOCO_ERR_NULL;
+    if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
+    if (int e = check_shape(M, n, stride)) return e;
+    if (anchor_stride != 0)
+        if (int e = check_shape(M, n, anchor_stride)) return e;
+    const int es = elem_size(theta_dtype);
+    if (!aligned_to(theta, es) || !aligned_to(anchor, 4)) return DILOCO_ERR_ALIGN;
+    Range r[2] = {{theta, extent_bytes(M, n, stride, es), true},
+                  {anchor, anchor_stride ? extent_bytes(M, n, anchor_stride, 4) : n * 4, false}};
+    if (int e = check_alias(r, 2)) return e;
+    if (n == 0) return DILOCO_OK;
+    const bool vec_ok = aligned_to(theta, 4 * es) && aligned_to(anchor, 16) &&
+                        (M == 1 || (stride % 4 == 0 && anchor_stride % 4 == 0));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (theta_dtype == DILOCO_F32)
+        return launch_reset<float>(static_cast<float*>(theta), anchor, M, n, stride, anchor_stride,
+                                   vec_ok, st);
+    return launch_reset<__bf16>(static_cast<__bf16*>(theta), anchor, M, n, stride, anchor_stride, vec_ok,
+                                st);
+}

@@ -1,0 +1,160 @@
+// Loss of the quadratic stand-in problem (deterministic two-stage fp64 reduction),
+// launch tuning, status strings.
+#include <cstring>
+
+#include "common.hpp"
+#include "diloco_sim.h"
+
+namespace diloco {
+
+Tuning& tuning() {
+    static Tuning t;
+    return t;
+}
+
+constexpr int kLossBlock = 256;
+constexpr int64_t kLossMaxBlocks = 8192;
+
+// Stage 1: workgroup b sums 0.5 h (tbar - theta*)^2 over its grid-strided share in fp64,
+// tbar = replica mean (left to right, fp64).  Fixed tree inside the workgroup.
+__global__ void quadratic_loss_partial_kernel(const float* __restrict__ theta, int M, int64_t n,
+                                              int64_t stride, const float* __restrict__ h,
+                                              const float* __restrict__ star,
+                                              double* __restrict__ partials, double inv_M) {
+    __shared__ double red[kLossBlock];
+    double acc = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kLossBlock + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * kLossBlock) {
+        double t = 0.0;
+        for (int m = 0; m < M; ++m) t += (double)theta[m * stride + i];
+        const double d = t * inv_M - (double)star[i];
+        acc += 0.5 * (double)h[i] * d * d;
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = kLossBlock / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partials[blockIdx.x] = red[0];
+}
+
+// Stage 2: one workgroup folds the partial sums, again in a fixed order.
+__global__ void quadratic_loss_final_kernel(const double* __restrict__ partials, int64_t count,
+                                            double* __restrict__ out) {
+    __shared__ double red[kLossBlock];
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < count; i += kLossBlock) acc += partials[i];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = kLossBlock / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = red[0];
+}
+
+__global__ __launch_bounds__(kMaxBlock) void stream_copy_kernel(float* __restrict__ dst,
+                                                                const float* __restrict__ src,
+                                                                int64_t n, int64_t per_xcd) {
+    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    const int64_t nvec = n >> 2;
+    if (v > nvec) return;
+    if (v == nvec) {
+        for (int64_t i = n & ~(int64_t)3; i < n; ++i) store1(dst + i, load1(src + i));
+        return;
+    }
+    store4(dst + (v << 2), load4(src + (v << 2)));
+}
+
+static int64_t loss_blocks(int64_t n) {
+    int64_t b = (n + kLossBlock * 4 - 1) / (kLossBlock * 4);
+    if (b < 1) b = 1;
+    if (b > kLossMaxBlocks) b = kLossMaxBlocks;
+    return b;
+}
+
+}  // namespace diloco
+
+using namespace diloco;
+
+extern "C" int64_t diloco_sim_loss_workspace(int64_t n) { return n < 0 ? 0 : loss_blocks(n); }
+
+extern "C" int diloco_sim_quadratic_loss(const float* theta, int M, int64_t n, int64_t stride,
+                                         const float* h, const float* theta_star, double* partials,
+                                         int64_t n_partials, double* loss_out, void* stream) {
+    if (!theta || !h || !theta_star || !partials || !loss_out) return DILOCO_ERR_NULL;
+    if (int e = check_shape(M, n, stride)) return e;
+    if (n_partials < loss_blocks(n)) return DILOCO_ERR_SHAPE;
+    if (!aligned_to(theta, 4) || !aligned_to(h, 4) || !aligned_to(theta_star, 4) ||
+        !aligned_to(partials, 8) || !aligned_to(loss_out, 8))
+        return DILOCO_ERR_ALIGN;
+    Range r[5] = {{theta, extent_bytes(M, n, stride, 4), false},
+                  {h, n * 4, false},
+                  {theta_star, n * 4, false},
+                  {partials, n_partials * 8, true},
+                  {loss_out, 8, true}};
+    if (int e = check_alias(r, 5)) return e;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t nb = loss_blocks(n);
+    hipLaunchKernelGGL(quadratic_loss_partial_kernel, dim3((unsigned)nb), dim3(kLossBlock), 0, st,
+                       theta, M, n, stride, h, theta_star, partials, 1.0 / M);
+    if (int e = launch_status()) return e;
+    hipLaunchKernelGGL(quadratic_loss_final_kernel, dim3(1), dim3(kLossBlock), 0, st, partials, nb,
+                       loss_out);
+    return launch_status();
+}
+
+extern "C" int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream) {
+    if (!dst || !src) return DILOCO_ERR_NULL;
+    if (n < 0 || n > ((int64_t)1 << 60)) return DILOCO_ERR_SHAPE;
+    if (!aligned_to(dst, 16) || !aligned_to(src, 16)) return DILOCO_ERR_ALIGN;
+    Range r[2] = {{dst, n * 4, true}, {src, n * 4, false}};
+    if (int e = check_alias(r, 2)) return e;
+    if (n == 0) return DILOCO_OK;
+    const int block = tuning().block;
+    const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
+    if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
+    Grid g = make_grid(threads, block);
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(g.blocks), dim3(block), 0,
+                       static_cast<hipStream_t>(stream), dst, src, n, g.per_xcd);
+    return launch_status();
+}
+
+extern "C" int diloco_tune(const char* key, int value) {
+    if (!key) return DILOCO_ERR_NULL;
+    if (!std::strcmp(key, "block")) {
+        if (value < 64 || value > kMaxBlock || (value & (value - 1))) return DILOCO_ERR_HYPER;
+        tuning().block = value;
+        return DILOCO_OK;
+    }
+    if (!std::strcmp(key, "xcd_remap")) {
+        if (value != 0 && value != 1) return DILOCO_ERR_HYPER;
+        tuning().xcd_remap = value;
+        return DILOCO_OK;
+    }
+    return DILOCO_ERR_HYPER;
+}
+
+extern "C" int diloco_tune_get(const char* key) {
+    if (!key) return -1;
+    if (!std::strcmp(key, "block")) return tuning().block;
+    if (!std::strcmp(key, "xcd_remap")) return tuning().xcd_remap;
+    return -1;
+}
+
+extern "C" const char* diloco_strerror(int status) {
+    switch (status) {
+        case DILOCO_OK: return "ok";
+        case DILOCO_ERR_NULL: return "a required pointer is NULL";
+        case DILOCO_ERR_SHAPE: return "bad shape: M, n, stride or workspace size out of range";
+        case DILOCO_ERR_ALIGN: return "a pointer or stride is not aligned as required";
+        case DILOCO_ERR_DTYPE: return "unknown dtype or variant code";
+        case DILOCO_ERR_HYPER: return "hyper-parameter out of range or not finite";
+        case DILOCO_ERR_ALIAS: return "buffers overlap";
+        case DILOCO_ERR_LAUNCH: return "the HIP runtime refused the launch";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int diloco_version(void) { return 100; }

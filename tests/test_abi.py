@@ -1,0 +1,172 @@
+"""Boundary tests that need no GPU: the shared library loads, exports every symbol the
+headers declare, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_12996_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return B.lib()
+
+
+def declared_functions():
+    names = []
+    for hdr in ("diloco.h", "diloco_sim.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(diloco_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    names = declared_functions()
+    assert {"diloco_inner_adamw", "diloco_outer_sync", "diloco_outer_eager", "diloco_reset"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in include/ but not exported"
+        assert name in B.SIGNATURES, f"{name} has no ctypes signature"
+    assert set(B.SIGNATURES) == set(names)
+
+
+def test_version_and_strerror(lib):
+    assert lib.diloco_version() >= 100
+    texts = {lib.diloco_strerror(c) for c in range(8)}
+    assert len(texts) == 8 and all(texts)
+    assert lib.diloco_strerror(1234) == b"unknown status"
+
+
+# fake, suitably aligned, non-overlapping device addresses: validation never dereferences
+P = [0x7000_0000_0000 + k * 0x1000_0000 for k in range(8)]
+
+
+def eager(lib, theta=P[0], dt=0, M=2, n=64, stride=64, a=P[1], u=P[2], pl=P[3], ss=64, pm=P[4],
+          lr=0.7, mu=0.9, nest=1, var=0, apply=1):
+    return lib.diloco_outer_eager(theta, dt, M, n, stride, a, u, pl, ss, pm, lr, mu, nest, var, apply, None)
+
+
+def test_outer_eager_validation(lib):
+    assert eager(lib, n=0) == B.OK                      # empty input: no-op, nothing launched
+    assert eager(lib, theta=None) == B.ERR_NULL
+    assert eager(lib, pm=None) == B.ERR_NULL
+    assert eager(lib, dt=7) == B.ERR_DTYPE
+    assert eager(lib, var=2) == B.ERR_DTYPE
+    assert eager(lib, M=0) == B.ERR_SHAPE
+    assert eager(lib, M=70000) == B.ERR_SHAPE
+    assert eager(lib, n=-1) == B.ERR_SHAPE
+    assert eager(lib, stride=63) == B.ERR_SHAPE          # rows would overlap
+    assert eager(lib, ss=10) == B.ERR_SHAPE
+    assert eager(lib, n=1 << 61) == B.ERR_SHAPE
+    assert eager(lib, mu=1.0) == B.ERR_HYPER
+    assert eager(lib, mu=-0.1) == B.ERR_HYPER
+    assert eager(lib, lr=float("nan")) == B.ERR_HYPER
+    assert eager(lib, lr=float("inf")) == B.ERR_HYPER
+    assert eager(lib, a=P[1] + 2) == B.ERR_ALIGN         # fp32 pointer not 4-byte aligned
+    assert eager(lib, theta=P[0] + 1, dt=1) == B.ERR_ALIGN
+    assert eager(lib, a=P[0]) == B.ERR_ALIAS             # anchor on top of theta
+    assert eager(lib, pm=P[3] + 64) == B.ERR_ALIAS       # prev_mean inside prev_local
+    assert eager(lib, u=P[1] + 4 * 100) == B.ERR_ALIAS   # vel overlaps anchor's second row
+
+
+def test_outer_sync_validation(lib):
+    def f(theta=P[0], dt=0, M=2, n=64, stride=64, a=P[1], u=P[2], mo=None, lr=0.7, mu=0.9):
+        return lib.diloco_outer_sync(theta, dt, M, n, stride, a, u, mo, lr, mu, 1, None)
+    assert f(n=0) == B.OK
+    assert f(a=None) == B.ERR_NULL
+    assert f(dt=3) == B.ERR_DTYPE
+    assert f(M=-1) == B.ERR_SHAPE
+    assert f(stride=8) == B.ERR_SHAPE
+    assert f(mu=1.5) == B.ERR_HYPER
+    assert f(u=P[2] + 1) == B.ERR_ALIGN
+    assert f(mo=P[1]) == B.ERR_ALIAS
+    assert f(u=P[1] + 16) == B.ERR_ALIAS
+
+
+def test_inner_adamw_validation(lib):
+    def f(th=P[0], m1=P[1], m2=P[2], g=P[3], M=2, n=64, stride=64, pd=0, gd=0, lr=4e-4, b1=0.9,
+          b2=0.95, eps=1e-8, wd=0.1, step=1):
+        return lib.diloco_inner_adamw(th, m1, m2, g, M, n, stride, pd, gd, lr, b1, b2, eps, wd, step, None)
+    assert f(n=0) == B.OK
+    assert f(g=None) == B.ERR_NULL
+    assert f(pd=2) == B.ERR_DTYPE
+    assert f(gd=-1) == B.ERR_DTYPE
+    assert f(n=-5) == B.ERR_SHAPE
+    assert f(step=0) == B.ERR_HYPER
+    assert f(b1=1.0) == B.ERR_HYPER
+    assert f(b2=-0.5) == B.ERR_HYPER
+    assert f(eps=0.0) == B.ERR_HYPER
+    assert f(wd=-1.0) == B.ERR_HYPER
+    assert f(lr=float("nan")) == B.ERR_HYPER
+    assert f(m1=P[1] + 2) == B.ERR_ALIGN
+    assert f(th=P[0] + 2, m1=P[1] + 2, m2=P[2] + 2, pd=1, n=0) == B.OK   # bf16: 2-byte aligned is fine
+    assert f(g=P[0]) == B.ERR_ALIAS
+    assert f(m2=P[1]) == B.ERR_ALIAS
+
+
+def test_reset_validation(lib):
+    def f(th=P[0], dt=0, M=2, n=64, stride=64, a=P[1], astride=0):
+        return lib.diloco_reset(th, dt, M, n, stride, a, astride, None)
+    assert f(n=0) == B.OK
+    assert f(a=None) == B.ERR_NULL
+    assert f(dt=9) == B.ERR_DTYPE
+    assert f(astride=5) == B.ERR_SHAPE
+    assert f(a=P[0] + 4 * 64) == B.ERR_ALIAS
+
+
+def test_sim_validation_and_tuning(lib):
+    def q(th=P[0], m1=P[1], m2=P[2], M=2, n=64, stride=64, h=P[3], star=P[4], noise=0.1, seed=1,
+          base=0, step=1):
+        return lib.diloco_sim_quadratic_inner(th, m1, m2, M, n, stride, h, star, noise, seed, base,
+                                              4e-4, 0.9, 0.95, 1e-8, 0.0, step, None)
+    assert q(n=0) == B.OK
+    assert q(h=None) == B.ERR_NULL
+    assert q(base=2) == B.ERR_SHAPE
+    assert q(noise=-1.0) == B.ERR_HYPER
+    assert q(th=P[0] + 4) == B.ERR_ALIGN
+    assert lib.diloco_sim_loss_workspace(0) == 1
+    assert lib.diloco_sim_loss_workspace(1 << 26) == 8192
+    assert lib.diloco_sim_quadratic_loss(P[0], 2, 64, 64, P[1], P[2], P[3], 0, P[4], None) == B.ERR_SHAPE
+    assert lib.diloco_sim_quadratic_loss(P[0], 2, 64, 64, P[1], P[2], None, 1, P[4], None) == B.ERR_NULL
+    old = lib.diloco_tune_get(b"block")
+    assert lib.diloco_tune(b"block", 128) == B.OK and lib.diloco_tune_get(b"block") == 128
+    assert lib.diloco_tune(b"block", 100) == B.ERR_HYPER
+    assert lib.diloco_tune(b"block", 2048) == B.ERR_HYPER
+    assert lib.diloco_tune(b"nope", 1) == B.ERR_HYPER
+    assert lib.diloco_tune(b"block", old) == B.OK
+    assert lib.diloco_tune_get(b"nope") == -1
+
+
+def test_binding_raises_with_status_text(lib):
+    class FakeTensor:
+        """Stands in for a device tensor: the call must fail in validation, before any launch."""
+        def __init__(self, ptr, shape, dtype):
+            self._p, self.shape, self.dtype = ptr, shape, dtype
+        def data_ptr(self):
+            return self._p
+        def dim(self):
+            return len(self.shape)
+        def stride(self, k):
+            return self.shape[1] if k == 0 else 1
+        def numel(self):
+            return self.shape[0] * (self.shape[1] if len(self.shape) > 1 else 1)
+    import torch
+    th = FakeTensor(P[0], (2, 64), torch.float32)
+    a = FakeTensor(P[0], (2, 64), torch.float32)      # aliases theta
+    u = FakeTensor(P[2], (2, 64), torch.float32)
+    pl = FakeTensor(P[3], (2, 64), torch.float32)
+    pm = FakeTensor(P[4], (64,), torch.float32)
+    with pytest.raises(B.DilocoError) as ei:
+        B.outer_eager(th, a, u, pl, pm, outer_lr=0.7, outer_momentum=0.9, stream=_NullStream())
+    assert ei.value.status == B.ERR_ALIAS and "overlap" in str(ei.value)
+
+
+class _NullStream:
+    cuda_stream = 0

@@ -1,0 +1,271 @@
+"""Per-call parity of the HIP library against the CPU checker, through the C ABI.
+
+Every case draws seeded inputs on the CPU, widens them exactly to float64 for the checker,
+uploads the same values, runs one library call and compares every output buffer element by
+element.  fp32 buffers are held to 1e-6, bf16 buffers to 4e-3 (tests/util.py).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_12996_amd as d
+from oracle import diloco_oracle as O
+from paper_2502_12996_amd import workloads as W
+from tests.util import TOL_BF16, TOL_F32, assert_close, rel_err
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+ETA, MU = 0.7, 0.9
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    assert d.version() >= 100
+    yield
+    torch.cuda.synchronize()
+
+
+def wl_for(M, n, bf16=False):
+    return W.Workload("case", M=M, n=n, theta_dtype="bf16" if bf16 else "f32")
+
+
+def run_eager_case(M, n, *, bf16=False, variant="eager", apply=True, nesterov=True, pad=0, seed=1,
+                   misalign=0):
+    """One diloco_outer_eager call against the checker; returns the worst error."""
+    wl = wl_for(M, n, bf16)
+    stride = n + pad
+    st = W.outer_state(wl, n, seed=seed, stride=stride + misalign)
+    if misalign:   # shift every buffer by `misalign` elements: still element-aligned, not 16-byte aligned
+        st = {k: (v[:, misalign:] if v.dim() == 2 else v) for k, v in st.items()}
+    ref = {k: W.to_f64(v[..., :n]) for k, v in st.items()}
+    fn = O.outer_eager if variant == "eager" else O.outer_delayed
+    fn(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU,
+       nesterov, apply)
+    full = {k: v.to(DEV) for k, v in W.outer_state(wl, n, seed=seed, stride=stride + misalign).items()}
+    g = {k: (v[:, misalign:] if (misalign and v.dim() == 2) else v) for k, v in full.items()}
+    before = {k: v.clone() for k, v in full.items()}
+    d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], n=n,
+                  outer_lr=ETA, outer_momentum=MU, nesterov=nesterov,
+                  variant=d.EAGER if variant == "eager" else d.DELAYED, apply_update=apply)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for k in ref:
+        got = W.to_f64(g[k][..., :n])
+        tol = TOL_BF16 if (bf16 and k == "theta") else TOL_F32
+        worst = max(worst, assert_close(got, ref[k], tol, f"{variant} M={M} n={n} {k}") / tol)
+        # columns outside [0, n) of every row (padding, and the skipped leading elements) untouched
+        if g[k].dim() == 2 and (pad or misalign):
+            assert torch.equal(full[k][:, misalign + n:], before[k][:, misalign + n:]), k
+            assert torch.equal(full[k][:, :misalign], before[k][:, :misalign]), k
+    # re-seeding: the replica holds exactly its outer parameters (rounded to bf16 if stored so)
+    want_theta = g["anchor"][:, :n].to(g["theta"].dtype)
+    assert torch.equal(g["theta"][:, :n], want_theta)
+    return worst
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 16, 33])
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 63, 64, 65, 1000, (1 << 16) + 1])
+def test_eager_sizes_and_replica_counts(M, n):
+    run_eager_case(M, n)
+
+
+@pytest.mark.parametrize("variant", ["eager", "delayed"])
+@pytest.mark.parametrize("apply", [True, False])
+@pytest.mark.parametrize("nesterov", [True, False])
+@pytest.mark.parametrize("M", [2, 8, 6])
+def test_eager_variants_and_first_boundary(variant, apply, nesterov, M):
+    run_eager_case(M, 70_003, variant=variant, apply=apply, nesterov=nesterov, seed=3)
+
+
+@pytest.mark.parametrize("M", [1, 2, 8, 7])
+@pytest.mark.parametrize("variant,apply", [("eager", True), ("delayed", True), ("eager", False)])
+def test_eager_bf16_workers(M, variant, apply):
+    run_eager_case(M, 50_001, bf16=True, variant=variant, apply=apply, seed=5)
+
+
+@pytest.mark.parametrize("M", [2, 8, 5, 70])
+def test_eager_padded_stride_and_elementwise_path(M):
+    run_eager_case(M, 4097, pad=60, seed=9)            # padded rows, still 16-byte aligned
+    run_eager_case(M, 4097, pad=2, seed=9)             # stride not a multiple of 4: element-wise path
+    run_eager_case(M, 4097, pad=7, misalign=1, seed=9)  # base pointers off by one element
+    run_eager_case(M, 1031, pad=7, misalign=1, bf16=True, seed=9)
+
+
+def test_eager_large_M_paths_agree_bitwise():
+    """Register, LDS-staged and element-wise kernels promise the same arithmetic in the same
+    order: M = 8 through the register kernel equals M = 8 through the element-wise kernel."""
+    n, M = 33_333, 8
+    wl = wl_for(M, n)
+    a = {k: v.to(DEV) for k, v in W.outer_state(wl, n, seed=11, stride=n + 2).items()}   # odd stride
+    b = {k: v.to(DEV) for k, v in W.outer_state(wl, n, seed=11, stride=n + 3).items()}   # multiple of 4
+    for s in (a, b):
+        d.outer_eager(s["theta"], s["anchor"], s["vel"], s["prev_local"], s["prev_mean"], n=n,
+                      outer_lr=ETA, outer_momentum=MU)
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k][..., :n], b[k][..., :n]), k
+
+
+def test_eager_empty_input_is_a_noop():
+    wl = wl_for(2, 8)
+    g = {k: v.to(DEV) for k, v in W.outer_state(wl, 8, seed=2).items()}
+    before = {k: v.clone() for k, v in g.items()}
+    d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], n=0,
+                  outer_lr=ETA, outer_momentum=MU)
+    torch.cuda.synchronize()
+    for k in g:
+        assert torch.equal(g[k], before[k])
+
+
+# ------------------------------------------------------------------ standard outer step
+@pytest.mark.parametrize("M", [1, 2, 3, 8, 33])
+@pytest.mark.parametrize("n", [1, 5, 64, 65, 4099, (1 << 16) + 3])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_sync_outer_step(M, n, bf16):
+    wl = wl_for(M, n, bf16)
+    st = W.outer_state(wl, n, seed=13)
+    theta, a, u = st["theta"], st["anchor"][0].clone(), st["vel"][0].clone()
+    rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
+    rmean = O.outer_standard(rt, ra, ru, ETA, MU, True)
+    gt, ga, gu = theta.to(DEV), a.to(DEV), u.to(DEV)
+    gm = torch.empty(n, device=DEV)
+    d.outer_sync(gt, ga, gu, mean_out=gm, outer_lr=ETA, outer_momentum=MU)
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(ga), ra, TOL_F32, "sync anchor")
+    assert_close(W.to_f64(gu), ru, TOL_F32, "sync vel")
+    assert_close(W.to_f64(gm), rmean, TOL_F32, "sync mean")
+    assert_close(W.to_f64(gt), rt, TOL_BF16 if bf16 else TOL_F32, "sync theta")
+    assert torch.equal(gt, ga.to(gt.dtype).expand(M, n))
+
+
+def test_sync_heavy_ball_misaligned_and_no_mean_out():
+    M, n = 3, 2050
+    wl = wl_for(M, n)
+    st = W.outer_state(wl, n + 1, seed=17)
+    theta, a, u = st["theta"][:, 1:], st["anchor"][0, 1:].clone(), st["vel"][0, 1:].clone()
+    rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
+    O.outer_standard(rt, ra, ru, 0.4, 0.5, False)
+    gfull = st["theta"].to(DEV)
+    gt = gfull[:, 1:]
+    gab, gub = torch.zeros(n + 1, device=DEV), torch.zeros(n + 1, device=DEV)
+    ga, gu = gab[1:], gub[1:]
+    ga.copy_(a)
+    gu.copy_(u)
+    d.outer_sync(gt, ga, gu, n=n, outer_lr=0.4, outer_momentum=0.5, nesterov=False)
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(ga), ra, TOL_F32, "anchor")
+    assert_close(W.to_f64(gu), ru, TOL_F32, "vel")
+    assert_close(W.to_f64(gt), rt, TOL_F32, "theta")
+    assert torch.equal(gfull[:, 0].cpu(), st["theta"][:, 0])
+
+
+def test_sync_momentum_off_lr_one_is_the_replica_average():
+    M, n = 8, 10_001
+    theta = W.normal((M, n), 0.02, tag="theta", seed=21)
+    want = theta.double().mean(dim=0).numpy()
+    gt = theta.to(DEV)
+    ga = W.normal((n,), 0.02, tag="anchor", seed=21).to(DEV)
+    gu = W.normal((n,), 1.0, tag="vel", seed=21).to(DEV)
+    d.outer_sync(gt, ga, gu, outer_lr=1.0, outer_momentum=0.0)
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(ga), want, TOL_F32, "replica average")
+
+
+# ------------------------------------------------------------------ reset
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shared", [True, False])
+@pytest.mark.parametrize("n,off", [(1, 0), (4099, 0), (4099, 1), (1 << 16, 0)])
+def test_reset(bf16, shared, n, off):
+    M = 3
+    dt = torch.bfloat16 if bf16 else torch.float32
+    a = W.normal((M, n + off), 0.02, tag="anchor", seed=23).to(DEV)
+    src = a[0, off:] if shared else a[:, off:]
+    base = torch.full((M, n + off + 5), 7.0, dtype=dt, device=DEV)
+    th = base[:, off:off + n]
+    for _ in range(2):   # idempotent
+        d.reset(th, src, n=n)
+    torch.cuda.synchronize()
+    want = (src.expand(M, n) if shared else src).to(dt)
+    assert torch.equal(th, want)
+    assert (base[:, off + n:] == 7.0).all() and (base[:, :off] == 7.0).all()
+
+
+# ------------------------------------------------------------------ inner AdamW
+@pytest.mark.parametrize("pdt,gdt", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32"), ("f32", "bf16")])
+@pytest.mark.parametrize("M,n,pad,off", [(1, 1, 0, 0), (2, 5, 3, 0), (4, 65, 0, 0), (3, 4099, 5, 1),
+                                         (8, (1 << 16) + 2, 2, 0), (2, 1 << 18, 0, 0)])
+@pytest.mark.parametrize("step", [1, 31])
+def test_inner_adamw(pdt, gdt, M, n, pad, off, step):
+    wl = wl_for(M, n, pdt == "bf16")
+    gd = torch.bfloat16 if gdt == "bf16" else torch.float32
+    st = W.adamw_state(wl, n + off, seed=29, stride=n + off + pad, grad_dtype=gd)
+    view = {k: v[:, off:off + n] for k, v in st.items()}
+    ref = {k: W.to_f64(v) for k, v in view.items()}
+    O.adamw_step(ref["theta"], ref["m1"], ref["m2"], ref["grad"], step, wl.lr, wl.beta1, wl.beta2,
+                 wl.eps, wl.weight_decay)
+    full = {k: v.to(DEV) for k, v in st.items()}
+    before = {k: v.clone() for k, v in full.items()}
+    g = {k: v[:, off:] for k, v in full.items()}
+    d.inner_adamw(g["theta"], g["m1"], g["m2"], g["grad"], n=n, lr=wl.lr, beta1=wl.beta1,
+                  beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay, step=step)
+    torch.cuda.synchronize()
+    tol = TOL_BF16 if pdt == "bf16" else TOL_F32
+    for k in ("theta", "m1", "m2"):
+        assert_close(W.to_f64(g[k][:, :n]), ref[k], tol, f"adamw {k}")
+        assert torch.equal(full[k][:, off + n:], before[k][:, off + n:])
+        assert torch.equal(full[k][:, :off], before[k][:, :off])
+    assert torch.equal(full["grad"], before["grad"])
+
+
+def test_inner_adamw_zero_state_first_step_and_zero_gradient():
+    M, n = 2, 1003
+    th = W.normal((M, n), 0.02, tag="theta", seed=31)
+    g = W.normal((M, n), 1e-2, tag="grad", seed=31)
+    g[0, :10] = 0.0
+    rt, rg = W.to_f64(th), W.to_f64(g)
+    r1, r2 = np.zeros((M, n)), np.zeros((M, n))
+    O.adamw_step(rt, r1, r2, rg, 1, 4e-4, 0.9, 0.95, 1e-8, 0.1)
+    gt, gg = th.to(DEV), g.to(DEV)
+    g1, g2 = torch.zeros((M, n), device=DEV), torch.zeros((M, n), device=DEV)
+    d.inner_adamw(gt, g1, g2, gg, lr=4e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1)
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(gt), rt, TOL_F32, "theta")
+    assert_close(W.to_f64(g1), r1, TOL_F32, "m1")
+    assert_close(W.to_f64(g2), r2, TOL_F32, "m2")
+    assert np.isfinite(W.to_f64(gt)).all()
+
+
+# ------------------------------------------------------------------ noisy quadratic
+@pytest.mark.parametrize("M,n,base", [(1, 7, 0), (4, 4099, 0), (3, 1 << 14, 1 << 26), (2, 1001, (1 << 33) + 4)])
+def test_quadratic_inner_step_and_loss(M, n, base):
+    wl = W.WORKLOADS["quadratic"]
+    h = W.log_uniform((n,), 1e-3, 1.0, tag="h", seed=37)
+    star = W.normal((n,), 1.0, tag="theta_star", seed=37)
+    ns = (n + 3) & ~3     # this entry point wants replica rows 16-byte aligned
+    th = W.normal((M, ns), 0.5, tag="theta", seed=37)
+    m1 = W.normal((M, ns), 0.1, tag="m1", seed=37)
+    m2 = W.normal((M, ns), 0.1, tag="m2", seed=37).square_()
+    rt, r1, r2 = (W.to_f64(x[:, :n]) for x in (th, m1, m2))
+    rh, rs = W.to_f64(h), W.to_f64(star)
+    seed, step = 0xC0FFEE, 17
+    O.quadratic_inner_step(rt, r1, r2, rh, rs, step, seed, wl.noise_std, wl.lr, wl.beta1, wl.beta2,
+                           wl.eps, 0.0, index_base=base)
+    gt, g1, g2, gh, gs = (x.to(DEV) for x in (th, m1, m2, h, star))
+    d.sim_quadratic_inner(gt, g1, g2, gh, gs, n=n, noise_std=wl.noise_std, seed=seed, index_base=base,
+                          lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=0.0,
+                          step=step)
+    part = torch.empty(d.sim_loss_workspace(n), dtype=torch.float64, device=DEV)
+    out = torch.empty(1, dtype=torch.float64, device=DEV)
+    d.sim_quadratic_loss(gt, gh, gs, part, out, n=n)
+    torch.cuda.synchronize()
+    assert torch.equal(gt[:, n:].cpu(), th[:, n:])
+    gt, g1, g2 = gt[:, :n], g1[:, :n], g2[:, :n]
+    # the gradient noise goes through fp32 log / sincos: a few 1e-7 relative on z, which AdamW's
+    # normalised step turns into the same relative error of the update (lr-sized), far inside 1e-6
+    assert_close(W.to_f64(gt), rt, TOL_F32, "theta")
+    assert_close(W.to_f64(g1), r1, TOL_F32, "m1")
+    assert_close(W.to_f64(g2), r2, TOL_F32, "m2")
+    want = O.quadratic_loss(O.mean_over_replicas(W.to_f64(gt)), rh, rs)
+    assert abs(out.item() - want) <= 1e-12 * max(want, 1e-300)
