@@ -32,14 +32,14 @@ def algorithmic_bytes(wl, n):
     return outer, inner
 
 
-def stored_traffic(workload):
+def stored_traffic(workload, layout):
     """HBM bytes per launch of the eager kernel, measured with rocprofv3 --pmc FETCH_SIZE and
     WRITE_SIZE (scaled by a copy kernel of known size) and kept in the committed summary."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_pmc_bench_%s.txt" % workload)
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith(workload + ".outer_eager_bytes_per_launch"):
+                if line.startswith("%s.outer_eager_%s_bytes_per_launch" % (workload, layout)):
                     return int(line.split("=")[1])
     except (OSError, ValueError):
         pass
@@ -83,8 +83,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="t550m")
-    ap.add_argument("--block", type=int, default=None, help="threads per workgroup")
-    ap.add_argument("--xcd-remap", type=int, default=None)
+    ap.add_argument("--layout", choices=("packed", "rows"), default="packed",
+                    help="outer state: library-packed tiles (default) or caller rows [M][stride]")
+    ap.add_argument("--autotune", type=int, default=1,
+                    help="pick workgroup size / XCD mapping per kernel before the warm-up (1) or keep defaults (0)")
     ap.add_argument("--pad", type=int, default=0, help="extra elements between replica rows")
     ap.add_argument("--cpu-sample", type=int, default=1 << 24,
                     help="parameter indices the CPU checker is timed on (0: skip)")
@@ -104,11 +106,6 @@ def main():
     wl = W.WORKLOADS[args.workload]
     M, n = wl.M, wl.n
     stride = n + args.pad
-    if args.block is not None:
-        d.tune("block", args.block)
-    if args.xcd_remap is not None:
-        d.tune("xcd_remap", args.xcd_remap)
-
     bf16 = wl.theta_dtype == "bf16"
     st = W.outer_state(wl, n, device=dev, stride=stride)
     ad = W.adamw_state(wl, n, device=dev, stride=stride,
@@ -117,16 +114,76 @@ def main():
     m1, m2, grad = ad["m1"], ad["m2"], ad["grad"]
     del ad["theta"]
     torch.cuda.empty_cache()
+    okw = dict(outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
+
+    def timed(fn, iters):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        ev[0].record()
+        for k in range(iters):
+            fn()
+            ev[k + 1].record()
+        torch.cuda.synchronize()
+        return sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(iters))
+
+    def autotune(fn):
+        """Fastest (block, xcd_remap) of the launch shapes the library offers, by median of 5."""
+        best = None
+        for block in (64, 128, 256, 512):
+            for xcd in (0, 1):
+                d.tune("block", block)
+                d.tune("xcd_remap", xcd)
+                fn()
+                t = timed(fn, 5)[2]
+                if best is None or t < best[0]:
+                    best = (t, block, xcd)
+        return best[1], best[2]
+
+    def run_rows():
+        d.outer_eager(theta, st["anchor"], st["vel"], st["prev_local"], st["prev_mean"], n=n, **okw)
+
+    def run_inner(t=31):
+        d.inner_adamw(theta, m1, m2, grad, n=n, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
+                      weight_decay=wl.weight_decay, step=t)
+
+    shape_default = (d.tune_get("block"), d.tune_get("xcd_remap"))
+    shape_rows = autotune(run_rows) if args.autotune else shape_default
+    shape_inner = autotune(run_inner) if args.autotune else shape_default
+
+    def set_shape(sh):
+        d.tune("block", sh[0])
+        d.tune("xcd_remap", sh[1])
+
+    # the eager step on caller-layout rows, timed on its own (secondary figure)
+    set_shape(shape_rows)
+    run_rows()
+    rows_ms = timed(run_rows, max(3, args.steps // 2))
+    rows_ms = sum(rows_ms) / len(rows_ms)
+
+    packed = args.layout == "packed"
+    if packed:
+        state = torch.empty(d.packed_state_elems(M, n), dtype=torch.float32, device=dev)
+        d.pack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
+                     prev_mean=st["prev_mean"])
+        torch.cuda.synchronize()
+        for k in ("anchor", "vel", "prev_local", "prev_mean"):
+            del st[k]
+        torch.cuda.empty_cache()
+
+        def run_outer():
+            d.outer_eager_packed(theta, state, n=n, **okw)
+        shape_outer = autotune(run_outer) if args.autotune else shape_default
+    else:
+        run_outer, shape_outer = run_rows, shape_rows
 
     def step(t, ev=None):
         if ev:
             ev[0].record()
-        d.inner_adamw(theta, m1, m2, grad, n=n, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
-                      weight_decay=wl.weight_decay, step=t)
+        set_shape(shape_inner)
+        run_inner(t)
         if ev:
             ev[1].record()
-        d.outer_eager(theta, st["anchor"], st["vel"], st["prev_local"], st["prev_mean"], n=n,
-                      outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
+        set_shape(shape_outer)
+        run_outer()
         if ev:
             ev[2].record()
 
@@ -144,10 +201,17 @@ def main():
     ms_step = (t1 - t0) * 1e3 / args.steps
     inner_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     outer_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    assert torch.isfinite(st["anchor"][:, :1024]).all()
+    if packed:
+        chk = torch.empty((M, 4096), device=dev)
+        d.unpack_state(state, M, 4096, anchor=chk)
+        assert torch.isfinite(chk).all()
+    else:
+        assert torch.isfinite(st["anchor"][:, :1024]).all()
 
     # practical ceiling: plain copy with the same access shape
-    src, dst = grad.view(-1)[:n] if not bf16 else st["vel"].view(-1)[:n], st["prev_local"].view(-1)[:n]
+    set_shape(shape_default)
+    cbuf = torch.empty(2 * n, dtype=torch.float32, device=dev)
+    src, dst = cbuf[:n], cbuf[n:]
     cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     for _ in range(3):
         d.sim_stream_copy(dst, src)
@@ -172,19 +236,27 @@ def main():
         "config": {"workload": f"{wl.name}: M={M} replicas x N={n} params, one AdamW sweep + one "
                                f"fused eager outer step per step",
                    "M": M, "N": n, "theta_dtype": wl.theta_dtype, "stride_pad": args.pad,
-                   "block": d.tune_get("block"), "xcd_remap": d.tune_get("xcd_remap")},
+                   "outer_state_layout": args.layout,
+                   "launch": {"outer": {"block": shape_outer[0], "xcd_remap": shape_outer[1]},
+                              "inner": {"block": shape_inner[0], "xcd_remap": shape_inner[1]}}},
         "outer_step": {"ms": outer_ms, "params_per_s": n / (outer_ms * 1e-3),
                        "worker_params_per_s": M * n / (outer_ms * 1e-3), "GBps": outer_gbps,
                        "frac_of_peak": outer_gbps / HBM_PEAK_GBPS},
+        "outer_step_rows_layout": {"ms": rows_ms, "GBps": outer_bytes / (rows_ms * 1e-3) / 1e9,
+                                   "frac_of_peak": outer_bytes / (rows_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                   "launch": {"block": shape_rows[0], "xcd_remap": shape_rows[1]}},
         "inner_step": {"ms": inner_ms, "worker_params_per_s": M * n / (inner_ms * 1e-3),
                        "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS},
         "copy_ceiling_GBps": copy_gbps,
-        "roofline": {"bound": "hbm", "kernel": "outer_eager_reg_kernel" , "achieved": outer_gbps,
+        "roofline": {"bound": "hbm", "kernel": "outer_eager_reg_kernel<%d, %s, eager, %s>" % (
+                         M, "bf16" if bf16 else "float", "TiledState" if packed else "RowState"), "achieved": outer_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": outer_gbps / HBM_PEAK_GBPS,
                      "frac_of_copy": outer_gbps / copy_gbps,
-                     "traffic": stored_traffic(wl.name)},
+                     "traffic": stored_traffic(wl.name, args.layout)},
     }
-    del st, ad, theta, m1, m2, grad, src, dst
+    del st, ad, theta, m1, m2, grad, src, dst, cbuf
+    if packed:
+        del state
     torch.cuda.empty_cache()
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample)

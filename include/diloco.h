@@ -125,6 +125,46 @@ int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, int64_t n, 
                        diloco_variant variant, int apply_update, void* stream);
 
 /*
+ * Packed outer state.  The eager / delayed outer step touches 3M+1 state streams per
+ * parameter index (outer parameters, velocity and previous local outer gradient of every
+ * replica, plus the previous mean).  Kept as separate [M][state_stride] rows they lie
+ * gigabytes apart, and a wavefront's 3M+1 accesses land in 3M+1 different pages.  The
+ * packed form is one buffer of diloco_packed_state_elems(M, n) floats laid out
+ * [tile][3M+1][DILOCO_STATE_TILE]: tile t holds, for parameter indices
+ * [t*4096, (t+1)*4096), stream 3m = outer parameters of replica m, 3m+1 = its velocity,
+ * 3m+2 = its previous local outer gradient, stream 3M = the previous mean.  The last
+ * tile is padded.  A window [off, off+n) of a larger model may be swept on its own when
+ * off is a multiple of DILOCO_STATE_TILE: pass state + (off/4096)*(3M+1)*4096.
+ * diloco_outer_eager_packed computes exactly what diloco_outer_eager computes (same
+ * arithmetic, same order, bit-identical results); only the addresses differ.
+ * state must be 16-byte aligned.
+ */
+#define DILOCO_STATE_TILE 4096
+
+/* Floats in the packed state of M replicas x n parameters; -1 for invalid M or n. */
+int64_t diloco_packed_state_elems(int M, int64_t n);
+
+/* rows -> packed.  anchor, vel, prev_local: [M][state_stride] fp32; prev_mean: [n] fp32;
+ * any of the four may be NULL, its streams are then left as they are. */
+int diloco_pack_state(float* state, int M, int64_t n, const float* anchor, const float* vel,
+                      const float* prev_local, int64_t state_stride, const float* prev_mean,
+                      void* stream);
+
+/* packed -> rows; NULL destinations are skipped. */
+int diloco_unpack_state(const float* state, int M, int64_t n, float* anchor, float* vel,
+                        float* prev_local, int64_t state_stride, float* prev_mean, void* stream);
+
+/* diloco_outer_eager on the packed state (Algorithm 3 lines 7-12 / Algorithm 2 lines 7-11). */
+int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                              int64_t stride, float* state,
+                              double outer_lr, double outer_momentum, int nesterov,
+                              diloco_variant variant, int apply_update, void* stream);
+
+/* theta_m <- outer parameters of replica m, read from the packed state. */
+int diloco_reset_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                        const float* state, void* stream);
+
+/*
  * theta_m <- anchor_m for every replica (the left-hand side of Algorithm 1 line 10 /
  * Algorithm 3 line 12 on its own).  anchor_stride == 0 broadcasts one shared [n]
  * buffer; otherwise anchor is [M][anchor_stride].  Idempotent.

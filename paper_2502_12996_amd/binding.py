@@ -37,6 +37,12 @@ SIGNATURES = {
     "diloco_outer_eager": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr,
                                     _c_i64, _c_ptr, _c_dbl, _c_dbl, _c_int, _c_int, _c_int, _c_ptr]),
     "diloco_reset": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_i64, _c_ptr]),
+    "diloco_packed_state_elems": (_c_i64, [_c_int, _c_i64]),
+    "diloco_pack_state": (_c_int, [_c_ptr, _c_int, _c_i64, _c_ptr, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr]),
+    "diloco_unpack_state": (_c_int, [_c_ptr, _c_int, _c_i64, _c_ptr, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr]),
+    "diloco_outer_eager_packed": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_dbl, _c_dbl,
+                                           _c_int, _c_int, _c_int, _c_ptr]),
+    "diloco_reset_packed": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr]),
     "diloco_sim_quadratic_inner": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_int, _c_i64, _c_i64, _c_ptr,
                                             _c_ptr, _c_dbl, ctypes.c_uint64, _c_i64, _c_dbl, _c_dbl,
                                             _c_dbl, _c_dbl, _c_dbl, _c_i64, _c_ptr]),
@@ -147,6 +153,53 @@ def outer_eager(theta, anchor, vel, prev_local, prev_mean, *, n=None, outer_lr, 
         _ptr(theta), _dtype_code(theta), M, n, _row_stride(theta), _ptr(anchor), _ptr(vel),
         _ptr(prev_local), ss, _ptr(prev_mean), outer_lr, outer_momentum, int(nesterov),
         int(variant), int(apply_update), _stream(stream)))
+
+
+def packed_state_elems(M: int, n: int) -> int:
+    return lib().diloco_packed_state_elems(M, n)
+
+
+def _state_stride(M, n, *rows):
+    ss = None
+    for r in rows:
+        if r is not None:
+            s = _row_stride(r)
+            assert ss is None or ss == s, "anchor, vel and prev_local must share one row stride"
+            ss = s
+    return n if ss is None else ss
+
+
+def pack_state(state, M, n, *, anchor=None, vel=None, prev_local=None, prev_mean=None,
+               stream=None) -> None:
+    """diloco_pack_state: rows ([M, state_stride] / [n]) -> packed buffer; None skips."""
+    _check("diloco_pack_state", lib().diloco_pack_state(
+        _ptr(state), M, n, _ptr(anchor), _ptr(vel), _ptr(prev_local),
+        _state_stride(M, n, anchor, vel, prev_local), _ptr(prev_mean), _stream(stream)))
+
+
+def unpack_state(state, M, n, *, anchor=None, vel=None, prev_local=None, prev_mean=None,
+                 stream=None) -> None:
+    """diloco_unpack_state: packed buffer -> rows; None skips."""
+    _check("diloco_unpack_state", lib().diloco_unpack_state(
+        _ptr(state), M, n, _ptr(anchor), _ptr(vel), _ptr(prev_local),
+        _state_stride(M, n, anchor, vel, prev_local), _ptr(prev_mean), _stream(stream)))
+
+
+def outer_eager_packed(theta, state, *, n=None, outer_lr, outer_momentum, nesterov=True,
+                       variant=EAGER, apply_update=True, stream=None) -> None:
+    """diloco_outer_eager_packed: theta [M, stride]; state from packed_state_elems(M, n)."""
+    M = theta.shape[0]
+    n = theta.shape[1] if n is None else n
+    _check("diloco_outer_eager_packed", lib().diloco_outer_eager_packed(
+        _ptr(theta), _dtype_code(theta), M, n, _row_stride(theta), _ptr(state), outer_lr,
+        outer_momentum, int(nesterov), int(variant), int(apply_update), _stream(stream)))
+
+
+def reset_packed(theta, state, *, n=None, stream=None) -> None:
+    M = theta.shape[0]
+    n = theta.shape[1] if n is None else n
+    _check("diloco_reset_packed", lib().diloco_reset_packed(
+        _ptr(theta), _dtype_code(theta), M, n, _row_stride(theta), _ptr(state), _stream(stream)))
 
 
 def reset(theta, anchor, *, n=None, stream=None) -> None:

@@ -7,6 +7,14 @@
 // m = 0..M-1 with no cross-lane traffic.  The whole outer step is one read-modify-write
 // pass: each byte of theta_m, the outer parameters, the velocity, the previous local
 // and previous averaged outer gradient is read once and written once.
+//
+// The per-replica outer state (outer parameters a_m, velocity u_m, previous local outer
+// gradient P_m) and the previous mean D are reached through a "state view":
+//   RowState    the caller's [M][state_stride] rows and [n] mean;
+//   TiledState  one library-defined buffer [tile][3M+1][4096 elements]: the 3M+1 state
+//               streams of 4096 consecutive parameters sit next to each other, so a
+//               wavefront's 3M+1 state accesses fall into one or two 2 MB pages instead of
+//               3M+1 pages that are gigabytes apart (fewer address-translation misses).
 #include "common.hpp"
 
 namespace diloco {
@@ -21,7 +29,35 @@ struct OuterScalars {
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
-// OuterOpt on one value: u <- mu u + G ; a <- a - (c_g G + c_u u).
+constexpr int kTileShift = 12;  // DILOCO_STATE_TILE = 4096 elements
+constexpr int64_t kTile = (int64_t)1 << kTileShift;
+static_assert(kTile == DILOCO_STATE_TILE, "header and kernels disagree on the state tile");
+
+struct RowState {
+    float* anchor;
+    float* vel;
+    float* P;
+    float* D;
+    int64_t ss;
+    __device__ __forceinline__ float* a(int m, int64_t i) const { return anchor + m * ss + i; }
+    __device__ __forceinline__ float* u(int m, int64_t i) const { return vel + m * ss + i; }
+    __device__ __forceinline__ float* p(int m, int64_t i) const { return P + m * ss + i; }
+    __device__ __forceinline__ float* d(int64_t i) const { return D + i; }
+};
+
+struct TiledState {
+    float* base;
+    int64_t S;  // streams per tile: 3M + 1
+    __device__ __forceinline__ float* at(int64_t s, int64_t i) const {
+        return base + ((((i >> kTileShift) * S + s) << kTileShift) | (i & (kTile - 1)));
+    }
+    __device__ __forceinline__ float* a(int m, int64_t i) const { return at(3 * m, i); }
+    __device__ __forceinline__ float* u(int m, int64_t i) const { return at(3 * m + 1, i); }
+    __device__ __forceinline__ float* p(int m, int64_t i) const { return at(3 * m + 2, i); }
+    __device__ __forceinline__ float* d(int64_t i) const { return at(S - 1, i); }
+};
+
+// OuterOpt on one value (or 4): u <- mu u + G ; a <- a - (c_g G + c_u u).
 template <typename T>
 __device__ __forceinline__ void outer_opt(T& a, T& u, T G, const OuterScalars& sc) {
     u = fma_(splat<T>(sc.mu), u, G);
@@ -35,68 +71,65 @@ __device__ __forceinline__ T eager_gradient(T d, T p, T Dold, const OuterScalars
 
 // ------------------------------------------------------------------ element-wise path
 // Runtime M, one parameter index, two passes over the replicas (the second re-reads
-// theta_m and anchor_m).  Serves misaligned buffers and the ragged tail of the vector
-// kernels; same arithmetic, same order.
-template <typename TT, int MODE>
-__device__ void eager_element(TT* theta, float* anchor, float* vel, float* P, float* D, int M,
-                              int64_t stride, int64_t sstride, int64_t i, const OuterScalars& sc) {
+// theta_m and a_m).  Serves misaligned buffers and the ragged tail of the vector kernels;
+// same arithmetic, same order.
+template <typename TT, int MODE, typename SV>
+__device__ void eager_element(TT* theta, SV sv, int M, int64_t stride, int64_t i,
+                              const OuterScalars& sc) {
     double s = 0.0;
     for (int m = 0; m < M; ++m) {
-        float a = load1(anchor + m * sstride + i);
+        float a = load1(sv.a(m, i));
         float th = load1(theta + m * stride + i);
         s += (double)(a - th);
     }
     const float dbar = (float)(s * sc.inv_M_d);
-    const float Dold = (MODE == MODE_RECORD) ? 0.f : load1(D + i);
+    const float Dold = (MODE == MODE_RECORD) ? 0.f : load1(sv.d(i));
     for (int m = 0; m < M; ++m) {
-        float a = load1(anchor + m * sstride + i);
+        float a = load1(sv.a(m, i));
         float th = load1(theta + m * stride + i);
         float d = a - th;
         if (MODE == MODE_RECORD) {
-            store1(anchor + m * sstride + i, th);
+            store1(sv.a(m, i), th);
         } else {
-            float u = load1(vel + m * sstride + i);
+            float u = load1(sv.u(m, i));
             float G = Dold;
-            if (MODE == MODE_EAGER) G = eager_gradient(d, load1(P + m * sstride + i), Dold, sc);
+            if (MODE == MODE_EAGER) G = eager_gradient(d, load1(sv.p(m, i)), Dold, sc);
             outer_opt(a, u, G, sc);
             store1(theta + m * stride + i, a);
-            store1(anchor + m * sstride + i, a);
-            store1(vel + m * sstride + i, u);
+            store1(sv.a(m, i), a);
+            store1(sv.u(m, i), u);
         }
-        store1(P + m * sstride + i, d);
+        store1(sv.p(m, i), d);
     }
-    store1(D + i, dbar);
+    store1(sv.d(i), dbar);
 }
 
-template <typename TT, int MODE>
-__global__ __launch_bounds__(kMaxBlock) void outer_eager_scalar_kernel(TT* theta, float* anchor, float* vel, float* P, float* D,
-                                          int M, int64_t n, int64_t stride, int64_t sstride,
-                                          OuterScalars sc, int64_t per_xcd) {
+template <typename TT, int MODE, typename SV>
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_scalar_kernel(TT* theta, SV sv, int M, int64_t n,
+                                                                       int64_t stride, OuterScalars sc,
+                                                                       int64_t per_xcd) {
     int64_t i = logical_block(per_xcd) * blockDim.x + threadIdx.x;
-    if (i < n) eager_element<TT, MODE>(theta, anchor, vel, P, D, M, stride, sstride, i, sc);
+    if (i < n) eager_element<TT, MODE, SV>(theta, sv, M, stride, i, sc);
 }
 
 // Tail of a vector kernel: the thread right after the last full vector sweeps n % 4 elements.
-template <typename TT, int MODE>
-__device__ __forceinline__ void eager_tail(TT* theta, float* anchor, float* vel, float* P, float* D,
-                                           int M, int64_t n, int64_t stride, int64_t sstride,
+template <typename TT, int MODE, typename SV>
+__device__ __forceinline__ void eager_tail(TT* theta, SV sv, int M, int64_t n, int64_t stride,
                                            const OuterScalars& sc) {
-    for (int64_t i = n & ~(int64_t)3; i < n; ++i)
-        eager_element<TT, MODE>(theta, anchor, vel, P, D, M, stride, sstride, i, sc);
+    for (int64_t i = n & ~(int64_t)3; i < n; ++i) eager_element<TT, MODE, SV>(theta, sv, M, stride, i, sc);
 }
 
 // ------------------------------------------------------------------ register path
-// M known at compile time: anchor_m and Delta_m of all replicas stay in registers between
-// the reduction and the update (2*M*4 VGPRs), nothing is read twice.
-template <int M, typename TT, int MODE>
-__global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restrict__ theta, float* __restrict__ anchor,
-                                       float* __restrict__ vel, float* __restrict__ P,
-                                       float* __restrict__ D, int64_t n, int64_t stride,
-                                       int64_t sstride, OuterScalars sc, int64_t per_xcd) {
+// M known at compile time: a_m and Delta_m of all replicas stay in registers between the
+// reduction and the update (2*M*4 VGPRs), nothing is read twice.
+template <int M, typename TT, int MODE, typename SV>
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restrict__ theta, SV sv, int64_t n,
+                                                                    int64_t stride, OuterScalars sc,
+                                                                    int64_t per_xcd) {
     const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     const int64_t nvec = n >> 2;
     if (v >= nvec) {
-        if (v == nvec) eager_tail<TT, MODE>(theta, anchor, vel, P, D, M, n, stride, sstride, sc);
+        if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, M, n, stride, sc);
         return;
     }
     const int64_t i = v << 2;
@@ -104,15 +137,15 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
     f4 Dold = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int m = 0; m < M; ++m) {
-        a[m] = load4(anchor + m * sstride + i);
+        a[m] = load4(sv.a(m, i));
         d[m] = load4(theta + m * stride + i);  // theta for now
     }
     if (MODE != MODE_RECORD) {
-        Dold = load4(D + i);
+        Dold = load4(sv.d(i));
 #pragma unroll
         for (int m = 0; m < M; ++m) {
-            u[m] = load4(vel + m * sstride + i);
-            if (MODE == MODE_EAGER) p[m] = load4(P + m * sstride + i);
+            u[m] = load4(sv.u(m, i));
+            if (MODE == MODE_EAGER) p[m] = load4(sv.p(m, i));
         }
     }
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
@@ -131,34 +164,33 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
 #pragma unroll
     for (int m = 0; m < M; ++m) {
         if (MODE == MODE_RECORD) {
-            store4(anchor + m * sstride + i, th[m]);
+            store4(sv.a(m, i), th[m]);
         } else {
             f4 G = Dold;
             if (MODE == MODE_EAGER) G = eager_gradient(d[m], p[m], Dold, sc);
             f4 an = a[m], un = u[m];
             outer_opt(an, un, G, sc);
             store4(theta + m * stride + i, an);
-            store4(anchor + m * sstride + i, an);
-            store4(vel + m * sstride + i, un);
+            store4(sv.a(m, i), an);
+            store4(sv.u(m, i), un);
         }
-        store4(P + m * sstride + i, d[m]);
+        store4(sv.p(m, i), d[m]);
     }
-    store4(D + i, dbar);
+    store4(sv.d(i), dbar);
 }
 
 // ------------------------------------------------------------------ LDS-staged path
-// Any M: anchor_m and Delta_m are parked in LDS (32 bytes per thread and replica) between
-// the two loops.  A thread only reads back what it wrote itself, so no barrier is needed.
-template <typename TT, int MODE>
-__global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restrict__ theta, float* __restrict__ anchor,
-                                       float* __restrict__ vel, float* __restrict__ P,
-                                       float* __restrict__ D, int M, int64_t n, int64_t stride,
-                                       int64_t sstride, OuterScalars sc, int64_t per_xcd) {
+// Any M: a_m and Delta_m are parked in LDS (32 bytes per thread and replica) between the two
+// loops.  A thread only reads back what it wrote itself, so no barrier is needed.
+template <typename TT, int MODE, typename SV>
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restrict__ theta, SV sv, int M,
+                                                                    int64_t n, int64_t stride, OuterScalars sc,
+                                                                    int64_t per_xcd) {
     extern __shared__ f4 stage[];  // [M][2][blockDim.x]
     const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     const int64_t nvec = n >> 2;
     if (v >= nvec) {
-        if (v == nvec) eager_tail<TT, MODE>(theta, anchor, vel, P, D, M, n, stride, sstride, sc);
+        if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, M, n, stride, sc);
         return;
     }
     const int64_t i = v << 2;
@@ -166,7 +198,7 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restri
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll 4
     for (int m = 0; m < M; ++m) {
-        f4 a = load4(anchor + m * sstride + i);
+        f4 a = load4(sv.a(m, i));
         f4 th = load4(theta + m * stride + i);
         f4 d = a - th;
         s0 += (double)d.x;
@@ -179,34 +211,36 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restri
     f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
                (float)(s3 * sc.inv_M_d)};
     f4 Dold = {0.f, 0.f, 0.f, 0.f};
-    if (MODE != MODE_RECORD) Dold = load4(D + i);
+    if (MODE != MODE_RECORD) Dold = load4(sv.d(i));
 #pragma unroll 4
     for (int m = 0; m < M; ++m) {
         f4 an = stage[(2 * m) * B + tid];
         f4 d = stage[(2 * m + 1) * B + tid];
         if (MODE == MODE_RECORD) {
-            store4(anchor + m * sstride + i, an);  // holds theta_m
+            store4(sv.a(m, i), an);  // holds theta_m
         } else {
-            f4 un = load4(vel + m * sstride + i);
+            f4 un = load4(sv.u(m, i));
             f4 G = Dold;
-            if (MODE == MODE_EAGER) G = eager_gradient(d, load4(P + m * sstride + i), Dold, sc);
+            if (MODE == MODE_EAGER) G = eager_gradient(d, load4(sv.p(m, i)), Dold, sc);
             outer_opt(an, un, G, sc);
             store4(theta + m * stride + i, an);
-            store4(anchor + m * sstride + i, an);
-            store4(vel + m * sstride + i, un);
+            store4(sv.a(m, i), an);
+            store4(sv.u(m, i), un);
         }
-        store4(P + m * sstride + i, d);
+        store4(sv.p(m, i), d);
     }
-    store4(D + i, dbar);
+    store4(sv.d(i), dbar);
 }
 
 // ------------------------------------------------------------------ standard DiLoCo
 // Shared outer parameters: nothing per replica has to survive the reduction, so a runtime
-// loop over m suffices.  VEC = 4 (128-bit) or 1 (element-wise).
+// loop over m suffices.
 template <typename TT>
 __global__ __launch_bounds__(kMaxBlock) void outer_sync_vec_kernel(TT* __restrict__ theta, float* __restrict__ anchor,
-                                      float* __restrict__ vel, float* __restrict__ mean_out, int M,
-                                      int64_t n, int64_t stride, OuterScalars sc, int64_t per_xcd) {
+                                                                   float* __restrict__ vel,
+                                                                   float* __restrict__ mean_out, int M, int64_t n,
+                                                                   int64_t stride, OuterScalars sc,
+                                                                   int64_t per_xcd) {
     const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     const int64_t nvec = n >> 2;
     if (v > nvec) return;
@@ -246,9 +280,10 @@ __global__ __launch_bounds__(kMaxBlock) void outer_sync_vec_kernel(TT* __restric
 }
 
 template <typename TT>
-__global__ __launch_bounds__(kMaxBlock) void outer_sync_scalar_kernel(TT* theta, float* anchor, float* vel, float* mean_out,
-                                         int M, int64_t n, int64_t stride, OuterScalars sc,
-                                         int64_t per_xcd) {
+__global__ __launch_bounds__(kMaxBlock) void outer_sync_scalar_kernel(TT* theta, float* anchor, float* vel,
+                                                                      float* mean_out, int M, int64_t n,
+                                                                      int64_t stride, OuterScalars sc,
+                                                                      int64_t per_xcd) {
     const int64_t i = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     if (i >= n) return;
     float a = load1(anchor + i), u = load1(vel + i);
@@ -262,28 +297,76 @@ __global__ __launch_bounds__(kMaxBlock) void outer_sync_scalar_kernel(TT* theta,
     if (mean_out) store1(mean_out + i, dbar);
 }
 
-// ------------------------------------------------------------------ reset
-template <typename TT>
-__global__ __launch_bounds__(kMaxBlock) void reset_vec_kernel(TT* __restrict__ theta, const float* __restrict__ anchor,
-                                 int64_t n, int64_t stride, int64_t astride, int64_t per_xcd) {
+// ------------------------------------------------------------------ reset (grid.y = replica)
+struct RowAnchor {
+    const float* anchor;
+    int64_t as;  // 0: one shared row
+    __device__ __forceinline__ const float* a(int m, int64_t i) const { return anchor + m * as + i; }
+};
+struct TiledAnchor {
+    const float* base;
+    int64_t S;
+    __device__ __forceinline__ const float* a(int m, int64_t i) const {
+        return base + ((((i >> kTileShift) * S + 3 * m) << kTileShift) | (i & (kTile - 1)));
+    }
+};
+
+template <typename TT, typename AV>
+__global__ __launch_bounds__(kMaxBlock) void reset_vec_kernel(TT* __restrict__ theta, AV av, int64_t n,
+                                                              int64_t stride, int64_t per_xcd) {
     const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     const int64_t nvec = n >> 2;
     const int m = blockIdx.y;
     if (v > nvec) return;
     if (v == nvec) {
-        for (int64_t i = n & ~(int64_t)3; i < n; ++i)
-            store1(theta + m * stride + i, load1(anchor + m * astride + i));
+        for (int64_t i = n & ~(int64_t)3; i < n; ++i) store1(theta + m * stride + i, load1(av.a(m, i)));
         return;
     }
     const int64_t i = v << 2;
-    store4(theta + m * stride + i, load4(anchor + m * astride + i));
+    store4(theta + m * stride + i, load4(av.a(m, i)));
 }
-template <typename TT>
-__global__ __launch_bounds__(kMaxBlock) void reset_scalar_kernel(TT* theta, const float* anchor, int64_t n, int64_t stride,
-                                    int64_t astride, int64_t per_xcd) {
+template <typename TT, typename AV>
+__global__ __launch_bounds__(kMaxBlock) void reset_scalar_kernel(TT* theta, AV av, int64_t n, int64_t stride,
+                                                                 int64_t per_xcd) {
     const int64_t i = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     const int m = blockIdx.y;
-    if (i < n) store1(theta + m * stride + i, load1(anchor + m * astride + i));
+    if (i < n) store1(theta + m * stride + i, load1(av.a(m, i)));
+}
+
+// ------------------------------------------------------------------ rows <-> tiled state
+// grid.y = state stream s (3m: a_m, 3m+1: u_m, 3m+2: P_m, 3M: D).  TO_TILED: rows -> tiled.
+// A NULL row buffer skips its streams.  VEC = 4 or 1.
+template <bool TO_TILED, int VEC>
+__global__ __launch_bounds__(kMaxBlock) void repack_kernel(float* tiled, float* anchor, float* vel, float* P,
+                                                           float* D, int M, int64_t n, int64_t ss,
+                                                           int64_t per_xcd) {
+    const int64_t e = (logical_block(per_xcd) * blockDim.x + threadIdx.x) * VEC;
+    if (e >= n) return;
+    const int s = blockIdx.y;
+    const int64_t S = 3 * M + 1;
+    float* row;
+    if (s == 3 * M) {
+        row = D;
+    } else {
+        const int m = s / 3, k = s - 3 * m;
+        float* b = k == 0 ? anchor : (k == 1 ? vel : P);
+        row = b ? b + m * ss : nullptr;
+    }
+    if (!row) return;
+    float* t = tiled + ((((e >> kTileShift) * S + s) << kTileShift) | (e & (kTile - 1)));
+    if (VEC == 4 && e + 4 <= n) {
+        if (TO_TILED)
+            store4(t, load4(row + e));
+        else
+            store4(row + e, load4(t));
+    } else {
+        for (int64_t j = 0; j < VEC && e + j < n; ++j) {
+            if (TO_TILED)
+                t[j] = row[e + j];
+            else
+                row[e + j] = t[j];
+        }
+    }
 }
 
 // ------------------------------------------------------------------ host dispatch
@@ -297,26 +380,25 @@ static OuterScalars make_scalars(int M, double lr, double mu, int nesterov) {
     return sc;
 }
 
-template <typename TT, int MODE>
-static int launch_eager(TT* theta, float* anchor, float* vel, float* P, float* D, int M, int64_t n,
-                        int64_t stride, int64_t sstride, const OuterScalars& sc, bool vec_ok,
-                        hipStream_t st) {
+template <typename TT, int MODE, typename SV>
+static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, const OuterScalars& sc,
+                        bool vec_ok, hipStream_t st) {
     const int block = tuning().block;
     if (!vec_ok) {
         if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
         Grid g = make_grid(n, block);
-        hipLaunchKernelGGL((outer_eager_scalar_kernel<TT, MODE>), dim3(g.blocks), dim3(block), 0, st,
-                           theta, anchor, vel, P, D, M, n, stride, sstride, sc, g.per_xcd);
+        hipLaunchKernelGGL((outer_eager_scalar_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(block), 0, st, theta,
+                           sv, M, n, stride, sc, g.per_xcd);
         return launch_status();
     }
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, 64)) return DILOCO_ERR_SHAPE;
-#define DILOCO_REG_CASE(MM)                                                                       \
-    case MM: {                                                                                    \
-        Grid g = make_grid(threads, block);                                                       \
-        hipLaunchKernelGGL((outer_eager_reg_kernel<MM, TT, MODE>), dim3(g.blocks), dim3(block), 0, \
-                           st, theta, anchor, vel, P, D, n, stride, sstride, sc, g.per_xcd);      \
-        return launch_status();                                                                   \
+#define DILOCO_REG_CASE(MM)                                                                               \
+    case MM: {                                                                                            \
+        Grid g = make_grid(threads, block);                                                               \
+        hipLaunchKernelGGL((outer_eager_reg_kernel<MM, TT, MODE, SV>), dim3(g.blocks), dim3(block), 0, st, \
+                           theta, sv, n, stride, sc, g.per_xcd);                                          \
+        return launch_status();                                                                           \
     }
     switch (M) {
         DILOCO_REG_CASE(1)
@@ -337,37 +419,37 @@ static int launch_eager(TT* theta, float* anchor, float* vel, float* P, float* D
     const int64_t lds = (int64_t)b * 32 * M;
     if (lds <= lds_max) {
         if (lds > 48 * 1024 &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&outer_eager_lds_kernel<TT, MODE>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&outer_eager_lds_kernel<TT, MODE, SV>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return DILOCO_ERR_LAUNCH;
         Grid g = make_grid(threads, b);
-        hipLaunchKernelGGL((outer_eager_lds_kernel<TT, MODE>), dim3(g.blocks), dim3(b), (size_t)lds,
-                           st, theta, anchor, vel, P, D, M, n, stride, sstride, sc, g.per_xcd);
+        hipLaunchKernelGGL((outer_eager_lds_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(b), (size_t)lds, st,
+                           theta, sv, M, n, stride, sc, g.per_xcd);
         return launch_status();
     }
     // M too large even for one wavefront per workgroup: element-wise two-pass kernel.
     if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(n, block);
-    hipLaunchKernelGGL((outer_eager_scalar_kernel<TT, MODE>), dim3(g.blocks), dim3(block), 0, st,
-                       theta, anchor, vel, P, D, M, n, stride, sstride, sc, g.per_xcd);
+    hipLaunchKernelGGL((outer_eager_scalar_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(block), 0, st, theta, sv,
+                       M, n, stride, sc, g.per_xcd);
     return launch_status();
 }
 
-template <typename TT>
-static int dispatch_eager(TT* theta, float* anchor, float* vel, float* P, float* D, int M, int64_t n,
-                          int64_t stride, int64_t sstride, const OuterScalars& sc, bool vec_ok,
-                          int mode, hipStream_t st) {
+template <typename TT, typename SV>
+static int dispatch_eager(void* theta, SV sv, int M, int64_t n, int64_t stride, const OuterScalars& sc,
+                          bool vec_ok, int mode, hipStream_t st) {
+    TT* th = static_cast<TT*>(theta);
     switch (mode) {
-        case MODE_RECORD:
-            return launch_eager<TT, MODE_RECORD>(theta, anchor, vel, P, D, M, n, stride, sstride, sc,
-                                                 vec_ok, st);
-        case MODE_EAGER:
-            return launch_eager<TT, MODE_EAGER>(theta, anchor, vel, P, D, M, n, stride, sstride, sc,
-                                                vec_ok, st);
-        default:
-            return launch_eager<TT, MODE_DELAYED>(theta, anchor, vel, P, D, M, n, stride, sstride, sc,
-                                                  vec_ok, st);
+        case MODE_RECORD: return launch_eager<TT, MODE_RECORD, SV>(th, sv, M, n, stride, sc, vec_ok, st);
+        case MODE_EAGER: return launch_eager<TT, MODE_EAGER, SV>(th, sv, M, n, stride, sc, vec_ok, st);
+        default: return launch_eager<TT, MODE_DELAYED, SV>(th, sv, M, n, stride, sc, vec_ok, st);
     }
+}
+
+static int64_t packed_elems(int M, int64_t n) { return ((n + kTile - 1) >> kTileShift) * (3 * (int64_t)M + 1) * kTile; }
+
+static int mode_of(int variant, int apply_update) {
+    return !apply_update ? MODE_RECORD : (variant == DILOCO_EAGER ? MODE_EAGER : MODE_DELAYED);
 }
 
 }  // namespace diloco
@@ -400,13 +482,90 @@ extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, 
                         aligned_to(prev_local, 16) && aligned_to(prev_mean, 16) &&
                         (M == 1 || (stride % 4 == 0 && state_stride % 4 == 0));
     const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
-    const int mode = !apply_update ? MODE_RECORD : (variant == DILOCO_EAGER ? MODE_EAGER : MODE_DELAYED);
+    const RowState sv{anchor, vel, prev_local, prev_mean, state_stride};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)
-        return dispatch_eager<float>(static_cast<float*>(theta), anchor, vel, prev_local, prev_mean, M,
-                                     n, stride, state_stride, sc, vec_ok, mode, st);
-    return dispatch_eager<__bf16>(static_cast<__bf16*>(theta), anchor, vel, prev_local, prev_mean, M, n,
-                                  stride, state_stride, sc, vec_ok, mode, st);
+        return dispatch_eager<float, RowState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);
+    return dispatch_eager<__bf16, RowState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);
+}
+
+extern "C" int64_t diloco_packed_state_elems(int M, int64_t n) {
+    if (M < 1 || M > DILOCO_MAX_REPLICAS || n < 0 || n > ((int64_t)1 << 40)) return -1;
+    return packed_elems(M, n);
+}
+
+extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                         int64_t stride, float* state, double outer_lr,
+                                         double outer_momentum, int nesterov, diloco_variant variant,
+                                         int apply_update, void* stream) {
+    if (!theta || !state) return DILOCO_ERR_NULL;
+    if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
+    if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
+    if (int e = check_shape(M, n, stride)) return e;
+    if (n > ((int64_t)1 << 40)) return DILOCO_ERR_SHAPE;
+    if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
+    const int es = elem_size(theta_dtype);
+    if (!aligned_to(theta, es) || !aligned_to(state, 16)) return DILOCO_ERR_ALIGN;
+    Range r[2] = {{theta, extent_bytes(M, n, stride, es), true}, {state, packed_elems(M, n) * 4, true}};
+    if (int e = check_alias(r, 2)) return e;
+    if (n == 0) return DILOCO_OK;
+    const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
+    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    const TiledState sv{state, 3 * (int64_t)M + 1};
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (theta_dtype == DILOCO_F32)
+        return dispatch_eager<float, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);
+    return dispatch_eager<__bf16, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);
+}
+
+// rows <-> tiled.  Any of anchor / vel / prev_local / prev_mean may be NULL (skipped).
+static int repack(bool to_tiled, float* state, int M, int64_t n, float* anchor, float* vel, float* prev_local,
+                  int64_t state_stride, float* prev_mean, void* stream) {
+    if (!state) return DILOCO_ERR_NULL;
+    if (int e = check_shape(M, n, state_stride)) return e;
+    if (n > ((int64_t)1 << 40) || 3 * M + 1 > 65535) return DILOCO_ERR_SHAPE;
+    if (!aligned_to(state, 16) || !aligned_to(anchor, 4) || !aligned_to(vel, 4) || !aligned_to(prev_local, 4) ||
+        !aligned_to(prev_mean, 4))
+        return DILOCO_ERR_ALIGN;
+    const int64_t rb = extent_bytes(M, n, state_stride, 4);
+    Range r[5] = {{state, packed_elems(M, n) * 4, to_tiled}, {anchor, rb, !to_tiled}, {vel, rb, !to_tiled},
+                  {prev_local, rb, !to_tiled}, {prev_mean, n * 4, !to_tiled}};
+    if (int e = check_alias(r, 5)) return e;
+    if (n == 0) return DILOCO_OK;
+    const bool vec_ok = aligned_to(anchor, 16) && aligned_to(vel, 16) && aligned_to(prev_local, 16) &&
+                        aligned_to(prev_mean, 16) && (M == 1 || state_stride % 4 == 0);
+    const int block = tuning().block;
+    const int64_t threads = vec_ok ? (n + 3) >> 2 : n;
+    if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
+    Grid g = make_grid(threads, block);
+    dim3 grid(g.blocks, 3 * M + 1);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (to_tiled && vec_ok)
+        hipLaunchKernelGGL((repack_kernel<true, 4>), grid, dim3(block), 0, st, state, anchor, vel, prev_local,
+                           prev_mean, M, n, state_stride, g.per_xcd);
+    else if (to_tiled)
+        hipLaunchKernelGGL((repack_kernel<true, 1>), grid, dim3(block), 0, st, state, anchor, vel, prev_local,
+                           prev_mean, M, n, state_stride, g.per_xcd);
+    else if (vec_ok)
+        hipLaunchKernelGGL((repack_kernel<false, 4>), grid, dim3(block), 0, st, state, anchor, vel, prev_local,
+                           prev_mean, M, n, state_stride, g.per_xcd);
+    else
+        hipLaunchKernelGGL((repack_kernel<false, 1>), grid, dim3(block), 0, st, state, anchor, vel, prev_local,
+                           prev_mean, M, n, state_stride, g.per_xcd);
+    return launch_status();
+}
+
+extern "C" int diloco_pack_state(float* state, int M, int64_t n, const float* anchor, const float* vel,
+                                 const float* prev_local, int64_t state_stride, const float* prev_mean,
+                                 void* stream) {
+    return repack(true, state, M, n, const_cast<float*>(anchor), const_cast<float*>(vel),
+                  const_cast<float*>(prev_local), state_stride, const_cast<float*>(prev_mean), stream);
+}
+
+extern "C" int diloco_unpack_state(const float* state, int M, int64_t n, float* anchor, float* vel,
+                                   float* prev_local, int64_t state_stride, float* prev_mean, void* stream) {
+    return repack(false, const_cast<float*>(state), M, n, anchor, vel, prev_local, state_stride, prev_mean,
+                  stream);
 }
 
 template <typename TT>
@@ -454,19 +613,18 @@ extern "C" int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, i
                                vec_ok, st);
 }
 
-template <typename TT>
-static int launch_reset(TT* theta, const float* anchor, int M, int64_t n, int64_t stride,
-                        int64_t astride, bool vec_ok, hipStream_t st) {
+template <typename TT, typename AV>
+static int launch_reset(void* theta, AV av, int M, int64_t n, int64_t stride, bool vec_ok, hipStream_t st) {
     const int block = tuning().block;
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(threads, block);
     if (vec_ok)
-        hipLaunchKernelGGL((reset_vec_kernel<TT>), dim3(g.blocks, M), dim3(block), 0, st, theta, anchor,
-                           n, stride, astride, g.per_xcd);
+        hipLaunchKernelGGL((reset_vec_kernel<TT, AV>), dim3(g.blocks, M), dim3(block), 0, st,
+                           static_cast<TT*>(theta), av, n, stride, g.per_xcd);
     else
-        hipLaunchKernelGGL((reset_scalar_kernel<TT>), dim3(g.blocks, M), dim3(block), 0, st, theta,
-                           anchor, n, stride, astride, g.per_xcd);
+        hipLaunchKernelGGL((reset_scalar_kernel<TT, AV>), dim3(g.blocks, M), dim3(block), 0, st,
+                           static_cast<TT*>(theta), av, n, stride, g.per_xcd);
     return launch_status();
 }
 
@@ -485,10 +643,26 @@ extern "C" int diloco_reset(void* theta, diloco_dtype theta_dtype, int M, int64_
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(theta, 4 * es) && aligned_to(anchor, 16) &&
                         (M == 1 || (stride % 4 == 0 && anchor_stride % 4 == 0));
+    const RowAnchor av{anchor, anchor_stride};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (theta_dtype == DILOCO_F32)
-        return launch_reset<float>(static_cast<float*>(theta), anchor, M, n, stride, anchor_stride,
-                                   vec_ok, st);
-    return launch_reset<__bf16>(static_cast<__bf16*>(theta), anchor, M, n, stride, anchor_stride, vec_ok,
-                                st);
+    if (theta_dtype == DILOCO_F32) return launch_reset<float, RowAnchor>(theta, av, M, n, stride, vec_ok, st);
+    return launch_reset<__bf16, RowAnchor>(theta, av, M, n, stride, vec_ok, st);
+}
+
+extern "C" int diloco_reset_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                                   const float* state, void* stream) {
+    if (!theta || !state) return DILOCO_ERR_NULL;
+    if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
+    if (int e = check_shape(M, n, stride)) return e;
+    if (n > ((int64_t)1 << 40)) return DILOCO_ERR_SHAPE;
+    const int es = elem_size(theta_dtype);
+    if (!aligned_to(theta, es) || !aligned_to(state, 16)) return DILOCO_ERR_ALIGN;
+    Range r[2] = {{theta, extent_bytes(M, n, stride, es), true}, {state, packed_elems(M, n) * 4, false}};
+    if (int e = check_alias(r, 2)) return e;
+    if (n == 0) return DILOCO_OK;
+    const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
+    const TiledAnchor av{state, 3 * (int64_t)M + 1};
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (theta_dtype == DILOCO_F32) return launch_reset<float, TiledAnchor>(theta, av, M, n, stride, vec_ok, st);
+    return launch_reset<__bf16, TiledAnchor>(theta, av, M, n, stride, vec_ok, st);
 }

@@ -121,6 +121,40 @@ def test_reset_validation(lib):
     assert f(a=P[0] + 4 * 64) == B.ERR_ALIAS
 
 
+def test_packed_state_validation(lib):
+    assert lib.diloco_packed_state_elems(8, 4097) == 2 * 25 * 4096
+    assert lib.diloco_packed_state_elems(1, 0) == 0
+    assert lib.diloco_packed_state_elems(0, 5) == -1
+    assert lib.diloco_packed_state_elems(2, -1) == -1
+
+    def f(th=P[0], dt=0, M=2, n=64, stride=64, st=P[1], lr=0.7, mu=0.9, var=0):
+        return lib.diloco_outer_eager_packed(th, dt, M, n, stride, st, lr, mu, 1, var, 1, None)
+    assert f(n=0) == B.OK
+    assert f(st=None) == B.ERR_NULL
+    assert f(dt=5) == B.ERR_DTYPE
+    assert f(var=3) == B.ERR_DTYPE
+    assert f(M=0) == B.ERR_SHAPE
+    assert f(stride=3) == B.ERR_SHAPE
+    assert f(mu=1.0) == B.ERR_HYPER
+    assert f(st=P[1] + 4) == B.ERR_ALIGN          # the packed state must be 16-byte aligned
+    assert f(st=P[0] + 16) == B.ERR_ALIAS
+
+    def pk(st=P[0], M=2, n=64, a=P[1], u=P[2], pl=P[3], ss=64, pm=P[4], fn=None):
+        return (fn or lib.diloco_pack_state)(st, M, n, a, u, pl, ss, pm, None)
+    for fn in (lib.diloco_pack_state, lib.diloco_unpack_state):
+        assert pk(n=0, fn=fn) == B.OK
+        assert pk(st=None, fn=fn) == B.ERR_NULL
+        assert pk(ss=5, fn=fn) == B.ERR_SHAPE
+        assert pk(M=30000, ss=64, fn=fn) == B.ERR_SHAPE
+        assert pk(st=P[0] + 8, fn=fn) == B.ERR_ALIGN
+        assert pk(a=P[1] + 2, fn=fn) == B.ERR_ALIGN
+        assert pk(a=P[0], fn=fn) == B.ERR_ALIAS
+        assert pk(a=None, u=None, pl=None, pm=None, n=0, fn=fn) == B.OK
+    assert lib.diloco_reset_packed(P[0], 0, 2, 0, 64, P[1], None) == B.OK
+    assert lib.diloco_reset_packed(P[0], 0, 2, 64, 64, None, None) == B.ERR_NULL
+    assert lib.diloco_reset_packed(P[0], 0, 2, 64, 64, P[1] + 4, None) == B.ERR_ALIGN
+
+
 def test_sim_validation_and_tuning(lib):
     def q(th=P[0], m1=P[1], m2=P[2], M=2, n=64, stride=64, h=P[3], star=P[4], noise=0.1, seed=1,
           base=0, step=1):

@@ -297,3 +297,31 @@ def test_quadratic_forty_phases(variant, lr_div):
     np.testing.assert_allclose(losses, scaled, rtol=0.1)
     print(f"quadratic/{variant}/lr_div={lr_div}: loss {losses[0]:.4e} -> {losses[-1]:.4e}; worst window "
           f"loss deviation {worst_loss:.2e}, worst state error after {H * wl.phases} steps {worst_state:.2e}")
+
+
+def test_t550m_packed_state_eager_outer_step_per_call():
+    """Config 3 through the packed-state entry point, the launch the benchmark times."""
+    wl = W.WORKLOADS["t550m"]
+    M, n = wl.M, wl.n
+    st = W.outer_state(wl, n, device=DEV)
+    chunks = big_chunks(n) + [(4096 * 1000 - 100, 4096 * 1000 + 100)]     # straddles a tile boundary
+    ref = [{k: f64(v[..., lo:hi]) for k, v in st.items()} for (lo, hi) in chunks]
+    state = torch.empty(d.packed_state_elems(M, n), device=DEV)
+    d.pack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
+                 prev_mean=st["prev_mean"])
+    for k in ("anchor", "vel", "prev_local", "prev_mean"):
+        st[k].zero_()
+    d.outer_eager_packed(st["theta"], state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
+    d.unpack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
+                   prev_mean=st["prev_mean"])
+    torch.cuda.synchronize()
+    worst = 0.0
+    for r, (lo, hi) in zip(ref, chunks):
+        O.outer_eager(r["theta"], r["anchor"], r["vel"], r["prev_local"], r["prev_mean"],
+                      wl.outer_lr, wl.outer_momentum, True, True)
+        for k in r:
+            worst = max(worst, assert_close(f64(st[k][..., lo:hi]), r[k], TOL_F32, f"packed {k} [{lo},{hi})"))
+    assert torch.equal(st["theta"], st["anchor"])
+    print(f"t550m packed: worst per-call error {worst:.2e}")
+    del st, state
+    torch.cuda.empty_cache()

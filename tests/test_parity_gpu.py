@@ -269,3 +269,99 @@ def test_quadratic_inner_step_and_loss(M, n, base):
     assert_close(W.to_f64(g2), r2, TOL_F32, "m2")
     want = O.quadratic_loss(O.mean_over_replicas(W.to_f64(gt)), rh, rs)
     assert abs(out.item() - want) <= 1e-12 * max(want, 1e-300)
+
+
+# ------------------------------------------------------------------ packed (tile-interleaved) outer state
+def _rows(M, n, seed, bf16=False, pad=0):
+    return {k: v.to(DEV) for k, v in W.outer_state(wl_for(M, n, bf16), n, seed=seed, stride=n + pad).items()}
+
+
+@pytest.mark.parametrize("M", [1, 3, 8])
+@pytest.mark.parametrize("n,pad", [(1, 0), (4095, 1), (4096, 0), (4097, 3), (3 * 4096 + 5, 2), (70_003, 1)])
+def test_pack_unpack_roundtrip_and_layout(M, n, pad):
+    g = _rows(M, n, 41, pad=pad)
+    state = torch.full((d.packed_state_elems(M, n),), -7.0, device=DEV)
+    d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                 prev_mean=g["prev_mean"])
+    torch.cuda.synchronize()
+    # the documented layout: [tile][3M+1][4096]
+    S, T = 3 * M + 1, 4096
+    tiles = (n + T - 1) // T
+    v = state.view(tiles, S, T).cpu()
+    for m in range(M):
+        for k, name in enumerate(("anchor", "vel", "prev_local")):
+            rows = g[name][m, :n].cpu()
+            got = v[:, 3 * m + k, :].reshape(-1)[:n]
+            assert torch.equal(got, rows), (m, name)
+    assert torch.equal(v[:, 3 * M, :].reshape(-1)[:n], g["prev_mean"].cpu())
+    assert (v.reshape(tiles, S, T)[-1, :, n - (tiles - 1) * T:] == -7.0).all()   # padding untouched
+    out = {k: torch.zeros_like(x) for k, x in g.items() if k != "theta"}
+    d.unpack_state(state, M, n, anchor=out["anchor"], vel=out["vel"], prev_local=out["prev_local"],
+                   prev_mean=out["prev_mean"])
+    torch.cuda.synchronize()
+    for k in out:
+        assert torch.equal(out[k][..., :n], g[k][..., :n]), k
+        if out[k].dim() == 2 and pad:
+            assert (out[k][:, n:] == 0).all()
+    # partial pack: only the anchors, the rest of the state stays
+    before = state.clone()
+    d.pack_state(state, M, n, anchor=g["vel"])
+    torch.cuda.synchronize()
+    v2 = state.view(tiles, S, T).cpu()
+    assert torch.equal(v2[:, 0, :].reshape(-1)[:n], g["vel"][0, :n].cpu())
+    assert torch.equal(v2[:, 1, :], before.view(tiles, S, T)[:, 1, :].cpu())
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 8, 5, 16, 33])
+@pytest.mark.parametrize("n", [1, 5, 4095, 4097, 70_003])
+@pytest.mark.parametrize("variant,apply", [("eager", True), ("delayed", True), ("eager", False)])
+def test_eager_packed_is_bit_identical_to_rows(M, n, variant, apply):
+    bf16 = (M + n) % 2 == 0
+    rows = _rows(M, n, 43, bf16)
+    pk = _rows(M, n, 43, bf16)
+    state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+    d.pack_state(state, M, n, anchor=pk["anchor"], vel=pk["vel"], prev_local=pk["prev_local"],
+                 prev_mean=pk["prev_mean"])
+    var = d.EAGER if variant == "eager" else d.DELAYED
+    d.outer_eager(rows["theta"], rows["anchor"], rows["vel"], rows["prev_local"], rows["prev_mean"],
+                  outer_lr=ETA, outer_momentum=MU, variant=var, apply_update=apply)
+    d.outer_eager_packed(pk["theta"], state, outer_lr=ETA, outer_momentum=MU, variant=var,
+                         apply_update=apply)
+    d.unpack_state(state, M, n, anchor=pk["anchor"], vel=pk["vel"], prev_local=pk["prev_local"],
+                   prev_mean=pk["prev_mean"])
+    torch.cuda.synchronize()
+    for k in rows:
+        assert torch.equal(rows[k], pk[k]), k
+
+
+def test_eager_packed_against_the_checker_and_elementwise_path():
+    M, n = 8, 50_003
+    st = W.outer_state(wl_for(M, n), n, seed=47, stride=n + 2)      # odd theta stride: element-wise path
+    ref = {k: W.to_f64(v[..., :n]) for k, v in st.items()}
+    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU,
+                  True, True)
+    g = {k: v.to(DEV) for k, v in st.items()}
+    state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+    d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                 prev_mean=g["prev_mean"])
+    d.outer_eager_packed(g["theta"], state, n=n, outer_lr=ETA, outer_momentum=MU)
+    d.unpack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                   prev_mean=g["prev_mean"])
+    torch.cuda.synchronize()
+    for k in ref:
+        assert_close(W.to_f64(g[k][..., :n]), ref[k], TOL_F32, f"packed {k}")
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("n,pad", [(5, 0), (4097, 0), (20_001, 1)])
+def test_reset_packed(bf16, n, pad):
+    M = 3
+    g = _rows(M, n, 53, bf16, pad=pad)
+    state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+    d.pack_state(state, M, n, anchor=g["anchor"])
+    th = torch.full_like(g["theta"], 3.0)
+    d.reset_packed(th, state, n=n)
+    torch.cuda.synchronize()
+    assert torch.equal(th[:, :n], g["anchor"][:, :n].to(th.dtype))
+    if pad:
+        assert (th[:, n:] == 3.0).all()
