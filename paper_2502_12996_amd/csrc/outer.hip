@@ -212,7 +212,6 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restri
                (float)(s3 * sc.inv_M_d)};
     f4 Dold = {0.f, 0.f, 0.f, 0.f};
     if (MODE != MODE_RECORD) Dold = load4(sv.d(i));
-#pragma unroll 4
     for (int m = 0; m < M; ++m) {
         f4 an = stage[(2 * m) * B + tid];
         f4 d = stage[(2 * m + 1) * B + tid];
@@ -272,7 +271,6 @@ __global__ __launch_bounds__(kMaxBlock) void outer_sync_vec_kernel(TT* __restric
     f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
                (float)(s3 * sc.inv_M_d)};
     outer_opt(a, u, dbar, sc);
-#pragma unroll 8
     for (int m = 0; m < M; ++m) store4(theta + m * stride + i, a);
     store4(anchor + i, a);
     store4(vel + i, u);
