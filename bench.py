@@ -32,6 +32,10 @@ def algorithmic_bytes(wl, n):
     return outer, inner
 
 
+def outer_bytes_fn(wl, n):
+    return algorithmic_bytes(wl, n)[0]
+
+
 def stored_traffic(workload, layout):
     """HBM bytes per launch of the eager kernel, measured with rocprofv3 --pmc FETCH_SIZE and
     WRITE_SIZE (scaled by a copy kernel of known size) and kept in the committed summary."""
@@ -208,6 +212,28 @@ def main():
     else:
         assert torch.isfinite(st["anchor"][:, :1024]).all()
 
+    # next rows: the same outer step swept fragment by fragment (Streaming DiLoCo windows, one
+    # launch per group of 3 layers) and with bf16 outer gradients on the wire
+    extra = {}
+    if packed and wl.layers:
+        set_shape(shape_outer)
+        frs = W.fragments(wl.layers, wl.d_model, wl.vocab)
+        S = 3 * M + 1
+
+        def run_fragments():
+            for off, cnt in frs:
+                d.outer_eager_packed(theta[:, off:off + cnt], state[(off // 4096) * S * 4096:], n=cnt, **okw)
+        run_fragments()
+        fms = timed(run_fragments, 5)[2]
+        extra["outer_step_by_fragments"] = {"fragments": len(frs), "ms": fms,
+                                            "GBps": outer_bytes_fn(wl, n) / (fms * 1e-3) / 1e9}
+
+        def run_q():
+            d.outer_eager_packed(theta, state, n=n, variant=d.EAGER | d.COMM_BF16, **okw)
+        run_q()
+        qms = timed(run_q, 5)[2]
+        extra["outer_step_bf16_comm"] = {"ms": qms, "GBps": outer_bytes_fn(wl, n) / (qms * 1e-3) / 1e9}
+
     # practical ceiling: plain copy with the same access shape
     set_shape(shape_default)
     cbuf = torch.empty(2 * n, dtype=torch.float32, device=dev)
@@ -247,6 +273,7 @@ def main():
                                    "launch": {"block": shape_rows[0], "xcd_remap": shape_rows[1]}},
         "inner_step": {"ms": inner_ms, "worker_params_per_s": M * n / (inner_ms * 1e-3),
                        "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS},
+        **extra,
         "copy_ceiling_GBps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": "outer_eager_reg_kernel<%d, %s, eager, %s>" % (
                          M, "bf16" if bf16 else "float", "TiledState" if packed else "RowState"), "achieved": outer_gbps,

@@ -51,6 +51,17 @@ typedef enum {
     DILOCO_DELAYED = 1  /* Algorithm 2 line 11: Delta_prev                              */
 } diloco_variant;
 
+/*
+ * Quantised communication (Section 3.2, "Quantized Communication"): OR this flag into the
+ * `variant` argument and every replica's outer gradient is rounded to bfloat16 (nearest even)
+ * before it enters the mean, as if it had crossed the wire in bf16:
+ *   prev_mean <- (1/M) sum_m bf16(Delta_m),  prev_local_m <- bf16(Delta_m)  (what was sent, so
+ *   that next phase's eager combination removes exactly the replica's own stale share),
+ * while the replica's own fresh Delta_m enters its eager combination unrounded.  The paper's
+ * fp8 / fp4 formats and their scaling are defined in a work it cites and are not built.
+ */
+#define DILOCO_COMM_BF16 0x100
+
 typedef enum {
     DILOCO_OK = 0,
     DILOCO_ERR_NULL = 1,   /* a required pointer is NULL                                   */
@@ -163,6 +174,23 @@ int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, int M, int6
 /* theta_m <- outer parameters of replica m, read from the packed state. */
 int diloco_reset_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
                         const float* state, void* stream);
+
+/*
+ * Streaming DiLoCo schedule (Section 3 of the paper: all its experiments apply the outer
+ * step to fragments of the model, e.g. 3 consecutive layers, on different schedules).  The
+ * outer-step entry points accept any (pointer + offset, n) window, so a fragment is swept
+ * by passing its window; these host-side helpers only say WHEN.  The paper does not give
+ * the stagger; this library spreads the fragments evenly over the H inner steps:
+ * fragment f of F has its outer boundaries at the steps t >= 1 with
+ * t mod H == diloco_stream_offset(H, F, f) = floor(f*H/F).
+ * diloco_stream_due returns 1 if step t is such a boundary, 0 if not, -1 for bad arguments
+ * (H < 1, F < 1, f outside [0, F), t < 0).  diloco_stream_boundary_count returns how many
+ * boundaries fragment f has had up to and including step t (the first one is the one where
+ * Algorithms 2 and 3 apply no outer step), -1 for bad arguments.
+ */
+int64_t diloco_stream_offset(int64_t H, int F, int f);
+int diloco_stream_due(int64_t t, int64_t H, int F, int f);
+int64_t diloco_stream_boundary_count(int64_t t, int64_t H, int F, int f);
 
 /*
  * theta_m <- anchor_m for every replica (the left-hand side of Algorithm 1 line 10 /

@@ -98,21 +98,43 @@ def outer_standard(theta, a, u, eta, mu, nesterov=True):
 
 
 # --------------------------------------------------------------------------
+# Quantised communication (Section 3.2): the outer gradient a replica sends is rounded to
+# bfloat16.  Rounding is a decision about an integer code, so it is taken in the precision the
+# wire format is produced from: the float32 difference of the stored float32 parameters.
+# --------------------------------------------------------------------------
+def round_to_bf16(x):
+    """float32 -> bfloat16 (round to nearest, ties to even) -> back, on an array of finite values."""
+    bits = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    bits = (bits + np.uint64(0x7FFF) + ((bits >> np.uint64(16)) & np.uint64(1))) & np.uint64(0xFFFF0000)
+    return bits.astype(np.uint32).view(np.float32).astype(F64)
+
+
+def sent_outer_gradients(delta, a, theta, comm):
+    """What enters the all-reduce: Delta_m, or bf16(Delta_m) with Delta_m formed in float32."""
+    if comm == "f32":
+        return delta
+    assert comm == "bf16"
+    d32 = (np.asarray(a, np.float32) - np.asarray(theta, np.float32)).astype(np.float32)
+    return round_to_bf16(d32)
+
+
+# --------------------------------------------------------------------------
 # Algorithm 2: naive delayed outer gradients, per-replica outer parameters
 # --------------------------------------------------------------------------
-def outer_delayed(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True):
+def outer_delayed(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True, comm="f32"):
     """theta, a, u, P [M, n]; D [n].  apply_update=False is the t = H boundary,
     where the listing applies no outer step: the replica just continues from its
     own parameters, which become its next anchor."""
     delta = local_outer_gradients(a, theta)          # line 7
-    delta_bar = mean_over_replicas(delta)            # line 8 (arrives one phase later)
+    wire = sent_outer_gradients(delta, a, theta, comm)
+    delta_bar = mean_over_replicas(wire)             # line 8 (arrives one phase later)
     if apply_update:                                 # line 9: t > H
         for m in range(theta.shape[0]):
             nesterov_step(a[m], u[m], D, eta, mu, nesterov)   # lines 10-11 with Delta^(t-H)
     else:
         a[...] = theta
     theta[...] = a
-    P[...] = delta
+    P[...] = wire
     D[...] = delta_bar
 
 
@@ -125,11 +147,14 @@ def eager_combination(delta, P, D):
     return (delta - P) / M + D
 
 
-def outer_eager(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True):
+def outer_eager(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True, comm="f32"):
     """theta, a, u, P [M, n]; D [n].  All Delta~_m are formed from the old P and D
-    before either is overwritten."""
+    before either is overwritten.  With quantised communication P holds what the replica
+    sent, so that line 11 removes exactly its own stale share of D, and the fresh local
+    Delta_m enters unrounded (the replica has it in full precision)."""
     delta = local_outer_gradients(a, theta)          # line 7
-    delta_bar = mean_over_replicas(delta)            # line 8
+    wire = sent_outer_gradients(delta, a, theta, comm)
+    delta_bar = mean_over_replicas(wire)             # line 8
     if apply_update:                                 # line 9: t > H
         G = eager_combination(delta, P, D)           # lines 10-11
         for m in range(theta.shape[0]):
@@ -137,7 +162,7 @@ def outer_eager(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True):
     else:
         a[...] = theta
     theta[...] = a
-    P[...] = delta
+    P[...] = wire
     D[...] = delta_bar
 
 
@@ -210,11 +235,24 @@ def quadratic_inner_step(theta, m1, m2, h, theta_star, t, seed, noise_std,
 # --------------------------------------------------------------------------
 # Drivers: whole runs of Algorithms 1-3
 # --------------------------------------------------------------------------
+def stream_offset(H, F, f):
+    """Streaming DiLoCo (Section 3: every experiment applies the outer step to fragments of the
+    model on different schedules; the stagger itself is not given in the paper): fragment f of
+    F has its outer boundaries at the steps t >= 1 with t mod H == floor(f H / F)."""
+    return (f * H) // F
+
+
+def is_boundary(t, H, offset=0):
+    return t >= 1 and t % H == offset % H
+
+
 def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
                   lr, beta1, beta2, eps, weight_decay, eta, mu, nesterov=True,
-                  index_base=0, theta0=None):
+                  index_base=0, theta0=None, boundary_offset=0):
     """T = H * phases steps of Algorithm 1 ("standard"), 2 ("delayed") or 3 ("eager")
     on the noisy quadratic, starting from theta = theta0 (default 0) on every replica.
+    Outer boundaries fall on the steps t with t mod H == boundary_offset mod H (the listings
+    have boundary_offset = 0); the first one applies no outer step for Algorithms 2 and 3.
     Returns (state dict, losses) with losses[k] the loss after outer boundary k,
     evaluated at the replica mean of the outer parameters."""
     n = h.shape[0]
@@ -227,15 +265,32 @@ def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
     P = np.zeros((M, n), F64)
     D = np.zeros(n, F64)
     losses = []
+    boundaries = 0
     for t in range(1, H * phases + 1):
         quadratic_inner_step(theta, m1, m2, h, theta_star, t, seed, noise_std,
                              lr, beta1, beta2, eps, weight_decay, index_base)
-        if t % H == 0:
+        if is_boundary(t, H, boundary_offset):
+            boundaries += 1
             if variant == "standard":
                 outer_standard(theta, a, u, eta, mu, nesterov)
                 losses.append(quadratic_loss(a, h, theta_star))
             else:
                 step = outer_eager if variant == "eager" else outer_delayed
-                step(theta, a, u, P, D, eta, mu, nesterov, apply_update=(t > H))
+                step(theta, a, u, P, D, eta, mu, nesterov, apply_update=(boundaries > 1))
                 losses.append(quadratic_loss(mean_over_replicas(a), h, theta_star))
     return dict(theta=theta, a=a, u=u, P=P, D=D, m1=m1, m2=m2), losses
+
+
+def run_streaming_quadratic(variant, fragments, M, H, phases, h, theta_star, seed, noise_std,
+                            lr, beta1, beta2, eps, weight_decay, eta, mu, nesterov=True):
+    """The same run with the model cut into fragments [(offset, count), ...] that take their
+    outer steps on staggered schedules.  Every update of the path is element-wise, so a
+    fragment is simply its own run of the algorithm on its slice with its own boundary offset."""
+    F = len(fragments)
+    out = []
+    for f, (off, cnt) in enumerate(fragments):
+        st, _ = run_quadratic(variant, M, H, phases, h[off:off + cnt], theta_star[off:off + cnt],
+                              seed, noise_std, lr, beta1, beta2, eps, weight_decay, eta, mu,
+                              nesterov, index_base=off, boundary_offset=stream_offset(H, F, f))
+        out.append(st)
+    return out

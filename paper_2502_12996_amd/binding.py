@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdiloco.so")
 
 F32, BF16 = 0, 1
 EAGER, DELAYED = 0, 1
+COMM_BF16 = 0x100   # OR into `variant`: outer gradients cross the wire in bf16
 
 OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_HYPER, ERR_ALIAS, ERR_LAUNCH = range(8)
 
@@ -43,6 +44,9 @@ SIGNATURES = {
     "diloco_outer_eager_packed": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_dbl, _c_dbl,
                                            _c_int, _c_int, _c_int, _c_ptr]),
     "diloco_reset_packed": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr]),
+    "diloco_stream_offset": (_c_i64, [_c_i64, _c_int, _c_int]),
+    "diloco_stream_due": (_c_int, [_c_i64, _c_i64, _c_int, _c_int]),
+    "diloco_stream_boundary_count": (_c_i64, [_c_i64, _c_i64, _c_int, _c_int]),
     "diloco_sim_quadratic_inner": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_int, _c_i64, _c_i64, _c_ptr,
                                             _c_ptr, _c_dbl, ctypes.c_uint64, _c_i64, _c_dbl, _c_dbl,
                                             _c_dbl, _c_dbl, _c_dbl, _c_i64, _c_ptr]),
@@ -200,6 +204,24 @@ def reset_packed(theta, state, *, n=None, stream=None) -> None:
     n = theta.shape[1] if n is None else n
     _check("diloco_reset_packed", lib().diloco_reset_packed(
         _ptr(theta), _dtype_code(theta), M, n, _row_stride(theta), _ptr(state), _stream(stream)))
+
+
+def stream_offset(H: int, F: int, f: int) -> int:
+    return lib().diloco_stream_offset(H, F, f)
+
+
+def stream_due(t: int, H: int, F: int, f: int) -> bool:
+    r = lib().diloco_stream_due(t, H, F, f)
+    if r < 0:
+        raise DilocoError("diloco_stream_due", ERR_SHAPE, "bad schedule arguments")
+    return bool(r)
+
+
+def stream_boundary_count(t: int, H: int, F: int, f: int) -> int:
+    r = lib().diloco_stream_boundary_count(t, H, F, f)
+    if r < 0:
+        raise DilocoError("diloco_stream_boundary_count", ERR_SHAPE, "bad schedule arguments")
+    return r
 
 
 def reset(theta, anchor, *, n=None, stream=None) -> None:

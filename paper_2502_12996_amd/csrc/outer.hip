@@ -25,7 +25,16 @@ struct OuterScalars {
     float c_u;       // coefficient of the new velocity: lr*mu (Nesterov) or lr
     float inv_M;     // 1/M in fp32 (eager combination)
     double inv_M_d;  // 1/M in fp64 (mean)
+    int comm_bf16;   // outer gradients cross the wire in bf16 (Section 3.2)
 };
+
+// What a replica sends into the all-reduce: Delta_m itself, or Delta_m rounded to bf16.
+__device__ __forceinline__ float sent(float d, const OuterScalars& sc) {
+    return sc.comm_bf16 ? static_cast<float>(static_cast<__bf16>(d)) : d;
+}
+__device__ __forceinline__ f4 sent(f4 d, const OuterScalars& sc) {
+    return sc.comm_bf16 ? __builtin_convertvector(__builtin_convertvector(d, bf4), f4) : d;
+}
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
@@ -80,7 +89,7 @@ __device__ void eager_element(TT* theta, SV sv, int M, int64_t stride, int64_t i
     for (int m = 0; m < M; ++m) {
         float a = load1(sv.a(m, i));
         float th = load1(theta + m * stride + i);
-        s += (double)(a - th);
+        s += (double)sent(a - th, sc);
     }
     const float dbar = (float)(s * sc.inv_M_d);
     const float Dold = (MODE == MODE_RECORD) ? 0.f : load1(sv.d(i));
@@ -99,7 +108,7 @@ __device__ void eager_element(TT* theta, SV sv, int M, int64_t stride, int64_t i
             store1(sv.a(m, i), a);
             store1(sv.u(m, i), u);
         }
-        store1(sv.p(m, i), d);
+        store1(sv.p(m, i), sent(d, sc));
     }
     store1(sv.d(i), dbar);
 }
@@ -154,10 +163,11 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
     for (int m = 0; m < M; ++m) {
         th[m] = d[m];
         d[m] = a[m] - th[m];
-        s0 += (double)d[m].x;
-        s1 += (double)d[m].y;
-        s2 += (double)d[m].z;
-        s3 += (double)d[m].w;
+        const f4 q = sent(d[m], sc);
+        s0 += (double)q.x;
+        s1 += (double)q.y;
+        s2 += (double)q.z;
+        s3 += (double)q.w;
     }
     f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
                (float)(s3 * sc.inv_M_d)};
@@ -174,7 +184,7 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
             store4(sv.a(m, i), an);
             store4(sv.u(m, i), un);
         }
-        store4(sv.p(m, i), d[m]);
+        store4(sv.p(m, i), sent(d[m], sc));
     }
     store4(sv.d(i), dbar);
 }
@@ -201,10 +211,11 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restri
         f4 a = load4(sv.a(m, i));
         f4 th = load4(theta + m * stride + i);
         f4 d = a - th;
-        s0 += (double)d.x;
-        s1 += (double)d.y;
-        s2 += (double)d.z;
-        s3 += (double)d.w;
+        const f4 q = sent(d, sc);
+        s0 += (double)q.x;
+        s1 += (double)q.y;
+        s2 += (double)q.z;
+        s3 += (double)q.w;
         stage[(2 * m) * B + tid] = (MODE == MODE_RECORD) ? th : a;
         stage[(2 * m + 1) * B + tid] = d;
     }
@@ -226,7 +237,7 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restri
             store4(sv.a(m, i), an);
             store4(sv.u(m, i), un);
         }
-        store4(sv.p(m, i), d);
+        store4(sv.p(m, i), sent(d, sc));
     }
     store4(sv.d(i), dbar);
 }
@@ -368,8 +379,9 @@ __global__ __launch_bounds__(kMaxBlock) void repack_kernel(float* tiled, float* 
 }
 
 // ------------------------------------------------------------------ host dispatch
-static OuterScalars make_scalars(int M, double lr, double mu, int nesterov) {
+static OuterScalars make_scalars(int M, double lr, double mu, int nesterov, int comm_bf16 = 0) {
     OuterScalars sc;
+    sc.comm_bf16 = comm_bf16;
     sc.mu = (float)mu;
     sc.c_g = nesterov ? (float)lr : 0.f;
     sc.c_u = nesterov ? (float)(lr * mu) : (float)lr;
@@ -461,6 +473,8 @@ extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, 
                                   int apply_update, void* stream) {
     if (!theta || !anchor || !vel || !prev_local || !prev_mean) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
+    const int comm_bf16 = (variant & DILOCO_COMM_BF16) ? 1 : 0;
+    variant = static_cast<diloco_variant>(variant & ~DILOCO_COMM_BF16);
     if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
     if (int e = check_shape(M, n, stride)) return e;
     if (int e = check_shape(M, n, state_stride)) return e;
@@ -479,7 +493,7 @@ extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, 
     const bool vec_ok = aligned_to(theta, 4 * es) && aligned_to(anchor, 16) && aligned_to(vel, 16) &&
                         aligned_to(prev_local, 16) && aligned_to(prev_mean, 16) &&
                         (M == 1 || (stride % 4 == 0 && state_stride % 4 == 0));
-    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov, comm_bf16);
     const RowState sv{anchor, vel, prev_local, prev_mean, state_stride};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)
@@ -498,6 +512,8 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
                                          int apply_update, void* stream) {
     if (!theta || !state) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
+    const int comm_bf16 = (variant & DILOCO_COMM_BF16) ? 1 : 0;
+    variant = static_cast<diloco_variant>(variant & ~DILOCO_COMM_BF16);
     if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
     if (int e = check_shape(M, n, stride)) return e;
     if (n > ((int64_t)1 << 40)) return DILOCO_ERR_SHAPE;
@@ -508,7 +524,7 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
     if (int e = check_alias(r, 2)) return e;
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
-    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov, comm_bf16);
     const TiledState sv{state, 3 * (int64_t)M + 1};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)

@@ -121,6 +121,26 @@ extern "C" int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, v
     return launch_status();
 }
 
+// ---------------------------------------------------------------- streaming schedule (host only)
+static bool stream_args_ok(int64_t t, int64_t H, int F, int f) {
+    return H >= 1 && F >= 1 && f >= 0 && f < F && t >= 0 && H <= ((int64_t)1 << 40);
+}
+extern "C" int64_t diloco_stream_offset(int64_t H, int F, int f) {
+    if (!stream_args_ok(0, H, F, f)) return -1;
+    return ((int64_t)f * H) / F;
+}
+extern "C" int diloco_stream_due(int64_t t, int64_t H, int F, int f) {
+    if (!stream_args_ok(t, H, F, f)) return -1;
+    return (t >= 1 && t % H == diloco_stream_offset(H, F, f)) ? 1 : 0;
+}
+extern "C" int64_t diloco_stream_boundary_count(int64_t t, int64_t H, int F, int f) {
+    if (!stream_args_ok(t, H, F, f)) return -1;
+    const int64_t off = diloco_stream_offset(H, F, f);
+    // boundaries are off, off + H, off + 2H, ... restricted to steps >= 1
+    if (off == 0) return t / H;
+    return t < off ? 0 : (t - off) / H + 1;
+}
+
 extern "C" int diloco_tune(const char* key, int value) {
     if (!key) return DILOCO_ERR_NULL;
     if (!std::strcmp(key, "block")) {

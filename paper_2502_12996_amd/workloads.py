@@ -82,6 +82,23 @@ def tensor_table(layers: int, d: int, vocab: int) -> List[Tuple[str, int, int]]:
     return table
 
 
+def fragments(layers: int, d: int, vocab: int, layers_per_fragment: int = 3) -> List[Tuple[int, int]]:
+    """(offset, count) of the Streaming-DiLoCo fragments of the flat buffer: groups of
+    `layers_per_fragment` consecutive layers (the paper's simulations use 3); the embedding,
+    which the paper does not place, joins the last group."""
+    per_layer = 12 * d * d
+    out: List[Tuple[int, int]] = []
+    l = 0
+    while l < layers:
+        k = min(layers_per_fragment, layers - l)
+        out.append((l * per_layer, k * per_layer))
+        l += k
+    off, cnt = out[-1]
+    out[-1] = (off, cnt + vocab * d)
+    assert out[-1][0] + out[-1][1] == transformer_param_count(layers, d, vocab)
+    return out
+
+
 WORKLOADS: Dict[str, Workload] = {
     # config 1: oracle-in-seconds case, 10 outer phases of noisy workers
     "tiny": Workload("tiny", M=2, n=1 << 20, H=1, phases=10),

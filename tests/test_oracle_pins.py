@@ -454,3 +454,48 @@ def test_eager_run_single_replica_equals_standard_after_first_phase_from_same_st
     O.outer_standard(ts, as_, us, 0.7, 0.9, True)
     np.testing.assert_allclose(ae[0], as_, rtol=1e-12, atol=1e-16)
     np.testing.assert_allclose(ue[0], us, rtol=1e-12, atol=1e-16)
+
+
+# ------------------------------------------------ quantised communication ---
+def test_bf16_rounding_matches_the_library_conversion():
+    x = np.concatenate([rnd(5000, scale=1e-3), rnd(5000), np.array([0.0, -0.0, 1.0, 1.00390625,
+                        1.01171875, 3.3895314e38, 1e-40, -1e-40, 2.0 ** -126])]).astype(np.float32)
+    want = torch.tensor(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(O.round_to_bf16(x).astype(np.float32), want)
+    # ties go to even: 1 + 2^-8 is half way between 1 and 1 + 2^-7
+    assert O.round_to_bf16(np.float32(1.00390625)) == 1.0
+    assert O.round_to_bf16(np.float32(1.01171875)) == 1.015625
+
+
+@pytest.mark.parametrize("fn", [O.outer_eager, O.outer_delayed])
+def test_quantised_communication_keeps_the_stale_share_identity(fn):
+    """With bf16 on the wire the stored previous local gradient is what was sent, so the eager
+    combination of the NEXT phase is still the mean of the fresh local and the stale non-local
+    contributions (Section 2.3), now of the quantised ones; the stored mean is their mean."""
+    M, n = 3, 50
+    a0 = rnd(n, scale=0.02).astype(np.float32).astype(np.float64)
+    theta = (np.tile(a0, (M, 1)) - rnd(M, n, scale=1e-3)).astype(np.float32).astype(np.float64)
+    a, u, P, D = np.tile(a0, (M, 1)), np.zeros((M, n)), np.zeros((M, n)), np.zeros(n)
+    fn(theta.copy(), a, u, P, D, 0.7, 0.9, True, apply_update=False, comm="bf16")
+    sent = torch.tensor((a0[None] - theta).astype(np.float32)).to(torch.bfloat16).double().numpy()
+    np.testing.assert_array_equal(P, sent)
+    np.testing.assert_allclose(D, sent.mean(axis=0), rtol=1e-14, atol=0)
+    assert np.max(np.abs(P - (a0[None] - theta))) > 0           # it really rounded something
+    if fn is O.outer_eager:
+        fresh = rnd(M, n, scale=1e-3)
+        G = O.eager_combination(fresh, P, D)
+        for m in range(M):
+            others = sum(sent[k] for k in range(M) if k != m)
+            np.testing.assert_allclose(G[m], (fresh[m] + others) / M, rtol=1e-10, atol=1e-16)
+
+
+def test_full_precision_communication_is_the_default():
+    M, n = 2, 9
+    a0 = rnd(n)
+    th = np.tile(a0, (M, 1)) - rnd(M, n, scale=1e-3)
+    s1 = [th.copy(), np.tile(a0, (M, 1)), rnd(M, n), rnd(M, n), rnd(n)]
+    s2 = [x.copy() for x in s1]
+    O.outer_eager(*s1, 0.7, 0.9, True, True)
+    O.outer_eager(*s2, 0.7, 0.9, True, True, comm="f32")
+    for x, y in zip(s1, s2):
+        np.testing.assert_array_equal(x, y)

@@ -365,3 +365,44 @@ def test_reset_packed(bf16, n, pad):
     assert torch.equal(th[:, :n], g["anchor"][:, :n].to(th.dtype))
     if pad:
         assert (th[:, n:] == 3.0).all()
+
+
+# ------------------------------------------------------------------ bf16 on the wire (Section 3.2)
+@pytest.mark.parametrize("M", [1, 2, 8, 5, 33])
+@pytest.mark.parametrize("variant,apply", [("eager", True), ("delayed", True), ("eager", False)])
+@pytest.mark.parametrize("packed", [False, True])
+def test_eager_with_bf16_communication(M, variant, apply, packed):
+    n = 30_005
+    st = W.outer_state(wl_for(M, n), n, seed=59)
+    ref = {k: W.to_f64(v) for k, v in st.items()}
+    fn = O.outer_eager if variant == "eager" else O.outer_delayed
+    fn(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU, True,
+       apply, comm="bf16")
+    g = {k: v.to(DEV) for k, v in st.items()}
+    var = (d.EAGER if variant == "eager" else d.DELAYED) | d.COMM_BF16
+    if packed:
+        state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+        d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                     prev_mean=g["prev_mean"])
+        d.outer_eager_packed(g["theta"], state, outer_lr=ETA, outer_momentum=MU, variant=var,
+                             apply_update=apply)
+        d.unpack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                       prev_mean=g["prev_mean"])
+    else:
+        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"],
+                      outer_lr=ETA, outer_momentum=MU, variant=var, apply_update=apply)
+    torch.cuda.synchronize()
+    # what was sent is a bf16 code: bit-exact; everything else to the fp32 tolerance
+    assert np.array_equal(W.to_f64(g["prev_local"]), ref["prev_local"])
+    bf = g["prev_local"].to(torch.bfloat16).to(torch.float32)
+    assert torch.equal(bf, g["prev_local"])
+    for k in ref:
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"bf16 comm {variant} {k}")
+
+
+def test_unknown_variant_bits_are_rejected():
+    g = _rows(2, 64, 3)
+    with pytest.raises(d.DilocoError) as ei:
+        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"],
+                      outer_lr=ETA, outer_momentum=MU, variant=0x200)
+    assert ei.value.status == d.binding.ERR_DTYPE

@@ -1,0 +1,134 @@
+"""Streaming-DiLoCo fragment schedule (Section 3 of the paper: every experiment applies the outer
+step to fragments of the model on staggered schedules).  CPU: the host-side schedule helpers of
+the library against the checker's own statement of the rule, and the checker's streaming driver
+against the plain one.  GPU: a whole staggered run through window calls against the checker."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_12996_amd as d
+from oracle import diloco_oracle as O
+from paper_2502_12996_amd import workloads as W
+from tests.util import assert_close, rel_err
+
+
+def test_schedule_matches_the_checker_exactly():
+    for H in (1, 2, 7, 30, 100):
+        for F in (1, 2, 3, 8, 11):
+            for f in range(F):
+                assert d.stream_offset(H, F, f) == O.stream_offset(H, F, f)
+                count = 0
+                for t in range(0, 3 * H + 5):
+                    due = d.stream_due(t, H, F, f)
+                    assert due == O.is_boundary(t, H, O.stream_offset(H, F, f)), (t, H, F, f)
+                    count += int(due)
+                    assert d.stream_boundary_count(t, H, F, f) == count, (t, H, F, f)
+
+
+def test_schedule_properties_and_errors():
+    H, F = 30, 4
+    offs = [d.stream_offset(H, F, f) for f in range(F)]
+    assert offs == [0, 7, 15, 22] and len(set(offs)) == F      # spread evenly, all distinct
+    for f in range(F):   # every fragment: exactly one boundary in any H consecutive steps
+        for start in (1, 5, 31, 64):
+            assert sum(d.stream_due(t, H, F, f) for t in range(start, start + H)) == 1
+    assert not d.stream_due(0, H, F, 0)                         # t = 0 is not a step
+    lib = d.binding.lib()
+    assert lib.diloco_stream_due(5, 0, 2, 0) == -1
+    assert lib.diloco_stream_due(5, 10, 2, 2) == -1
+    assert lib.diloco_stream_due(-1, 10, 2, 0) == -1
+    assert lib.diloco_stream_offset(10, 0, 0) == -1
+    assert lib.diloco_stream_boundary_count(5, 10, 3, -1) == -1
+
+
+def test_fragments_partition_the_flat_buffer():
+    for (L, dm, V) in ((12, 768, 32768), (24, 1408, 32768), (7, 64, 512)):
+        fr = W.fragments(L, dm, V)
+        assert fr[0][0] == 0
+        for (o1, c1), (o2, _) in zip(fr, fr[1:]):
+            assert o1 + c1 == o2
+        assert fr[-1][0] + fr[-1][1] == W.transformer_param_count(L, dm, V)
+        assert len(fr) == -(-L // 3)
+
+
+QUAD = dict(seed=77, noise_std=0.1, lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0,
+            eta=0.7, mu=0.9)
+
+
+def test_checker_streaming_driver_reduces_to_the_plain_run():
+    n, M, H, phases = 40, 2, 6, 4
+    rng = np.random.default_rng(5)
+    h = np.exp(rng.uniform(np.log(1e-3), 0.0, n))
+    star = rng.standard_normal(n)
+    for variant in ("standard", "eager", "delayed"):
+        plain, _ = O.run_quadratic(variant, M, H, phases, h, star, **QUAD)
+        one = O.run_streaming_quadratic(variant, [(0, n)], M, H, phases, h, star, **QUAD)
+        for k in plain:
+            np.testing.assert_array_equal(one[0][k], plain[k])
+        # two fragments: the one with offset 0 is exactly the plain run restricted to its slice
+        two = O.run_streaming_quadratic(variant, [(0, 24), (24, 16)], M, H, phases, h, star, **QUAD)
+        for k in plain:
+            np.testing.assert_array_equal(two[0][k], plain[k][..., :24])
+        # the staggered one has seen a different number of outer steps: it must differ
+        assert np.max(np.abs(two[1]["a"] - plain["a"][..., 24:])) > 0
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant", ["eager_packed", "eager", "delayed", "standard"])
+def test_staggered_run_through_window_calls(variant):
+    DEV = "cuda:0"
+    L, dm, V = 6, 64, 512
+    M, H, phases = 2, 10, 6
+    n = W.transformer_param_count(L, dm, V)
+    frags = W.fragments(L, dm, V)
+    F = len(frags)
+    assert F == 2 and all(off % 4096 == 0 for off, _ in frags)
+    h = W.log_uniform((n,), 1e-3, 1.0, tag="h", seed=61, device=DEV)
+    star = W.normal((n,), 1.0, tag="theta_star", seed=61, device=DEV)
+    theta = torch.zeros((M, n), device=DEV)
+    m1, m2 = torch.zeros_like(theta), torch.zeros_like(theta)
+    shared = variant == "standard"
+    a = torch.zeros(n, device=DEV) if shared else torch.zeros((M, n), device=DEV)
+    u = torch.zeros_like(a)
+    P = torch.zeros((M, n), device=DEV)
+    D = torch.zeros(n, device=DEV)
+    S = 3 * M + 1
+    state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+    q = QUAD
+    for t in range(1, H * phases + 1):
+        d.sim_quadratic_inner(theta, m1, m2, h, star, noise_std=q["noise_std"], seed=q["seed"],
+                              lr=q["lr"], beta1=q["beta1"], beta2=q["beta2"], eps=q["eps"],
+                              weight_decay=0.0, step=t)
+        for f, (off, cnt) in enumerate(frags):
+            if not d.stream_due(t, H, F, f):
+                continue
+            apply = d.stream_boundary_count(t, H, F, f) > 1
+            th = theta[:, off:off + cnt]
+            kw = dict(n=cnt, outer_lr=q["eta"], outer_momentum=q["mu"])
+            if shared:
+                d.outer_sync(th, a[off:off + cnt], u[off:off + cnt], **kw)
+            elif variant == "eager_packed":
+                d.outer_eager_packed(th, state[(off // 4096) * S * 4096:], apply_update=apply, **kw)
+            else:
+                d.outer_eager(th, a[:, off:off + cnt], u[:, off:off + cnt], P[:, off:off + cnt],
+                              D[off:off + cnt], apply_update=apply,
+                              variant=d.DELAYED if variant == "delayed" else d.EAGER, **kw)
+    if variant == "eager_packed":
+        d.unpack_state(state, M, n, anchor=a, vel=u, prev_local=P, prev_mean=D)
+    torch.cuda.synchronize()
+    ov = {"eager_packed": "eager"}.get(variant, variant)
+    ref = O.run_streaming_quadratic(ov, frags, M, H, phases, W.to_f64(h), W.to_f64(star),
+                                    q["seed"], q["noise_std"], q["lr"], q["beta1"], q["beta2"],
+                                    q["eps"], 0.0, q["eta"], q["mu"])
+    worst = 0.0
+    for (off, cnt), r in zip(frags, ref):
+        sl = slice(off, off + cnt)
+        pairs = [("theta", theta[:, sl], r["theta"]), ("m1", m1[:, sl], r["m1"]), ("m2", m2[:, sl], r["m2"]),
+                 ("anchor", a[sl] if shared else a[:, sl], r["a"]), ("vel", u[sl] if shared else u[:, sl], r["u"])]
+        if not shared:
+            pairs += [("prev_local", P[:, sl], r["P"]), ("prev_mean", D[sl], r["D"])]
+        for name, g, want in pairs:
+            # 60 AdamW steps and up to 6 outer steps with fp32 state against float64 state:
+            # trajectory mode (measured 5e-6), not the per-call 1e-6 gate
+            worst = max(worst, assert_close(W.to_f64(g), want, 2e-5, f"{variant} fragment at {off} {name}"))
+    print(f"streaming/{variant}: worst trajectory error {worst:.2e}")
