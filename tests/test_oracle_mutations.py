@@ -1,0 +1,243 @@
+"""The pins must be able to fail: plausible mistakes are planted in the CPU checker (on the CPU
+only), one at a time, and the pin tests are re-run; every planted mistake has to trip at least
+one of them."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import diloco_oracle as O
+from tests import test_oracle_pins as P
+from tests import test_streaming as S
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+PINS = [
+    P.test_adamw_constant_gradient_closed_form,
+    P.test_adamw_first_step_is_sign_step,
+    P.test_adamw_zero_gradient_no_decay_is_identity,
+    lambda: P.test_adamw_trajectory_matches_torch_adamw(0.0),
+    lambda: P.test_adamw_trajectory_matches_torch_adamw(0.1),
+    P.test_nesterov_constant_gradient_closed_form,
+    P.test_zero_momentum_is_plain_sgd,
+    lambda: P.test_outer_optimizer_matches_torch_sgd(True),
+    lambda: P.test_outer_optimizer_matches_torch_sgd(False),
+    P.test_velocity_form_equals_lookahead_form_for_constant_lr,
+    P.test_standard_momentum_off_lr_one_gives_replica_average,
+    P.test_standard_trajectory_matches_torch_sgd_on_outer_params,
+    lambda: P.test_eager_combination_equals_mean_of_fresh_local_and_stale_others(3),
+    lambda: P.test_eager_combination_equals_mean_of_fresh_local_and_stale_others(1),
+    P.test_eager_with_stationary_outer_gradients_feeds_the_stale_mean,
+    P.test_single_replica_eager_call_equals_standard_call,
+    lambda: P.test_identical_replicas_stay_identical_and_local_gradient_is_the_mean(False),
+    lambda: P.test_identical_replicas_stay_identical_and_local_gradient_is_the_mean(True),
+    lambda: P.test_multi_phase_trajectory_by_brute_force("eager"),
+    lambda: P.test_multi_phase_trajectory_by_brute_force("delayed"),
+    P.test_delayed_is_nesterov_on_the_shifted_mean_sequence,
+    P.test_first_boundary_applies_no_outer_step,
+    P.test_reset_is_idempotent_and_broadcasts,
+    lambda: P.test_mix64_matches_published_splitmix64_outputs(GOLDEN),
+    P.test_noise_is_standard_normal_and_streams_are_independent,
+    P.test_quadratic_gradient_and_loss_fixed_points,
+    lambda: P.test_noise_free_quadratic_converges("eager"),
+    P.test_quadratic_run_single_replica_standard_matches_torch_optimizers,
+    P.test_bf16_rounding_matches_the_library_conversion,
+    lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_eager),
+    lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_delayed),
+    S.test_checker_streaming_driver_reduces_to_the_plain_run,
+]
+
+
+def caught():
+    for pin in PINS:
+        try:
+            pin()
+        except Exception:           # an assertion, or a crash the mistake provokes
+            return True
+    return False
+
+
+def test_the_unmodified_checker_passes_every_pin():
+    for pin in PINS:
+        pin()
+
+
+# ---- planted mistakes -----------------------------------------------------------------
+def nesterov_wrong_sign(a, u, G, eta, mu, nesterov=True):
+    u[...] = mu * u + G
+    a[...] = a + eta * (G + mu * u) if nesterov else a + eta * u
+
+
+def nesterov_stale_velocity(a, u, G, eta, mu, nesterov=True):
+    u_old = u.copy()
+    u[...] = mu * u + G
+    a[...] = a - eta * (G + mu * u_old) if nesterov else a - eta * u
+
+
+def nesterov_dampened(a, u, G, eta, mu, nesterov=True):
+    u[...] = mu * u + (1 - mu) * G
+    a[...] = a - eta * (G + mu * u) if nesterov else a - eta * u
+
+
+def nesterov_ignores_flag(a, u, G, eta, mu, nesterov=True):
+    u[...] = mu * u + G
+    a[...] = a - eta * (G + mu * u)
+
+
+def _adam(eps_inside=False, no_bias=False, coupled=False, decay_after=False, beta_swap=False):
+    def f(theta, m1, m2, g, t, lr, beta1, beta2, eps, wd):
+        if beta_swap:
+            beta1, beta2 = beta2, beta1
+        gg = g + wd * theta if coupled else g
+        m1[...] = beta1 * m1 + (1 - beta1) * gg
+        m2[...] = beta2 * m2 + (1 - beta2) * gg * gg
+        mh = m1 if no_bias else m1 / (1 - beta1 ** t)
+        vh = m2 if no_bias else m2 / (1 - beta2 ** t)
+        den = np.sqrt(vh + eps) if eps_inside else np.sqrt(vh) + eps
+        if coupled:
+            theta[...] = theta - lr * mh / den
+        elif decay_after:
+            theta[...] = theta - lr * mh / den
+            theta[...] = theta - lr * wd * theta
+        else:
+            theta[...] = theta - lr * (mh / den + wd * theta)
+    return f
+
+
+def eager_no_division(delta, Pp, D):
+    return (delta - Pp) + D
+
+
+def eager_plus_stale(delta, Pp, D):
+    return (delta + Pp) / delta.shape[0] + D
+
+
+def eager_drops_mean(delta, Pp, D):
+    return (delta - Pp) / delta.shape[0]
+
+
+def outer_eager_rotates_first(theta, a, u, Pp, D, eta, mu, nesterov=True, apply_update=True, comm="f32"):
+    delta = O.local_outer_gradients(a, theta)
+    wire = O.sent_outer_gradients(delta, a, theta, comm)
+    Pp[...] = wire
+    D[...] = O.mean_over_replicas(wire)
+    if apply_update:
+        G = O.eager_combination(delta, Pp, D)
+        for m in range(theta.shape[0]):
+            O.nesterov_step(a[m], u[m], G[m], eta, mu, nesterov)
+    else:
+        a[...] = theta
+    theta[...] = a
+
+
+def outer_eager_always_applies(theta, a, u, Pp, D, eta, mu, nesterov=True, apply_update=True, comm="f32"):
+    return ORIG["outer_eager"](theta, a, u, Pp, D, eta, mu, nesterov, True, comm)
+
+
+def outer_eager_rounds_local_too(theta, a, u, Pp, D, eta, mu, nesterov=True, apply_update=True, comm="f32"):
+    delta = O.local_outer_gradients(a, theta)
+    wire = O.sent_outer_gradients(delta, a, theta, comm)
+    dbar = O.mean_over_replicas(wire)
+    if apply_update:
+        G = O.eager_combination(delta, Pp, D)
+        for m in range(theta.shape[0]):
+            O.nesterov_step(a[m], u[m], G[m], eta, mu, nesterov)
+    else:
+        a[...] = theta
+    theta[...] = a
+    Pp[...] = delta          # stores the unrounded gradient although bf16 was sent
+    D[...] = dbar
+
+
+def outer_delayed_uses_fresh_mean(theta, a, u, Pp, D, eta, mu, nesterov=True, apply_update=True, comm="f32"):
+    delta = O.local_outer_gradients(a, theta)
+    wire = O.sent_outer_gradients(delta, a, theta, comm)
+    dbar = O.mean_over_replicas(wire)
+    if apply_update:
+        for m in range(theta.shape[0]):
+            O.nesterov_step(a[m], u[m], dbar, eta, mu, nesterov)
+    else:
+        a[...] = theta
+    theta[...] = a
+    Pp[...] = wire
+    D[...] = dbar
+
+
+def mean_forgets_division(delta):
+    return delta.sum(axis=0)
+
+
+def mean_wrong_divisor(delta):
+    return delta.sum(axis=0) / max(1, delta.shape[0] - 1)
+
+
+def local_wrong_sign(a, theta):
+    return theta - a
+
+
+def standard_no_reset(theta, a, u, eta, mu, nesterov=True):
+    delta = O.local_outer_gradients(a, theta)
+    dbar = O.mean_over_replicas(delta)
+    O.nesterov_step(a, u, dbar, eta, mu, nesterov)
+    return dbar
+
+
+def mix64_wrong_shift(x):
+    x = np.asarray(x, dtype=np.uint64).copy()
+    with np.errstate(over="ignore"):
+        x ^= x >> np.uint64(31)
+        x *= np.uint64(0xBF58476D1CE4E5B9)
+        x ^= x >> np.uint64(27)
+        x *= np.uint64(0x94D049BB133111EB)
+        x ^= x >> np.uint64(31)
+    return x
+
+
+def normal_without_factor_two(seed, t, m, idx):
+    return ORIG["standard_normal"](seed, t, m, idx) / np.sqrt(2.0)
+
+
+def normal_ignores_replica(seed, t, m, idx):
+    return ORIG["standard_normal"](seed, t, 0, idx)
+
+
+def bf16_truncates(x):
+    bits = np.asarray(x, dtype=np.float32).view(np.uint32) & np.uint32(0xFFFF0000)
+    return bits.view(np.float32).astype(np.float64)
+
+
+def boundary_ignores_offset(t, H, offset=0):
+    return t >= 1 and t % H == 0
+
+
+def quadratic_gradient_without_curvature(theta_m, h, theta_star, noise_std, seed, t, m, index_base=0):
+    idx = index_base + np.arange(theta_m.shape[-1], dtype=np.int64)
+    return (theta_m - theta_star) + noise_std * O.standard_normal(seed, t, m, idx)
+
+
+ORIG = {k: getattr(O, k) for k in dir(O) if callable(getattr(O, k)) and not k.startswith("_")}
+
+MUTATIONS = [
+    ("nesterov_step", nesterov_wrong_sign), ("nesterov_step", nesterov_stale_velocity),
+    ("nesterov_step", nesterov_dampened), ("nesterov_step", nesterov_ignores_flag),
+    ("adamw_step", _adam(eps_inside=True)), ("adamw_step", _adam(no_bias=True)),
+    ("adamw_step", _adam(coupled=True)), ("adamw_step", _adam(decay_after=True)),
+    ("adamw_step", _adam(beta_swap=True)),
+    ("eager_combination", eager_no_division), ("eager_combination", eager_plus_stale),
+    ("eager_combination", eager_drops_mean),
+    ("outer_eager", outer_eager_rotates_first), ("outer_eager", outer_eager_always_applies),
+    ("outer_eager", outer_eager_rounds_local_too),
+    ("outer_delayed", outer_delayed_uses_fresh_mean),
+    ("mean_over_replicas", mean_forgets_division), ("mean_over_replicas", mean_wrong_divisor),
+    ("local_outer_gradients", local_wrong_sign), ("outer_standard", standard_no_reset),
+    ("mix64", mix64_wrong_shift), ("standard_normal", normal_without_factor_two),
+    ("standard_normal", normal_ignores_replica), ("round_to_bf16", bf16_truncates),
+    ("is_boundary", boundary_ignores_offset),
+    ("quadratic_gradient", quadratic_gradient_without_curvature),
+]
+
+
+@pytest.mark.parametrize("name,bad", MUTATIONS, ids=[f"{n}:{f.__name__}:{i}" for i, (n, f) in enumerate(MUTATIONS)])
+def test_planted_mistake_is_caught(name, bad, monkeypatch):
+    monkeypatch.setattr(O, name, bad)
+    assert caught(), f"no pin notices the mistake planted in {name}"
