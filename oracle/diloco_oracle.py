@@ -32,6 +32,8 @@ trajectories, the paper's equivalent form of the eager combination (Section
 2.3: the mean of the fresh local and the stale non-local outer gradients),
 M = 1 and identical-worker reductions, the mu = 0, eta = 1 worker average, and
 published splitmix64 test vectors plus distribution tests for the noise.
+Parity unpinned: run_quadratic(overlap=2) against the paper, which gives no formula for the
+2-outer-steps overlap (the function is pinned to the reading stated in its docstring).
 """
 from __future__ import annotations
 
@@ -248,11 +250,16 @@ def is_boundary(t, H, offset=0):
 
 def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
                   lr, beta1, beta2, eps, weight_decay, eta, mu, nesterov=True,
-                  index_base=0, theta0=None, boundary_offset=0):
+                  index_base=0, theta0=None, boundary_offset=0, overlap=1):
     """T = H * phases steps of Algorithm 1 ("standard"), 2 ("delayed") or 3 ("eager")
     on the noisy quadratic, starting from theta = theta0 (default 0) on every replica.
     Outer boundaries fall on the steps t with t mod H == boundary_offset mod H (the listings
     have boundary_offset = 0); the first one applies no outer step for Algorithms 2 and 3.
+    overlap = 2 is the 2-outer-steps overlap of Section 3.2 ("Two-outer-steps overlap"), for
+    which the paper gives no formula (PARITY UNPINNED against the paper).  Reading: the
+    all-reduce launched at a boundary is consumed two boundaries later, i.e. Algorithms 2 and 3
+    with Delta_m^(t-2H), Delta^(t-2H) in place of Delta_m^(t-H), Delta^(t-H) and `if t > 2H`;
+    the two generations in flight live in two (P, D) slots used alternately.
     Returns (state dict, losses) with losses[k] the loss after outer boundary k,
     evaluated at the replica mean of the outer parameters."""
     n = h.shape[0]
@@ -262,8 +269,8 @@ def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
     shared = variant == "standard"
     a = theta[0].copy() if shared else theta.copy()
     u = np.zeros_like(a)
-    P = np.zeros((M, n), F64)
-    D = np.zeros(n, F64)
+    Ps = [np.zeros((M, n), F64) for _ in range(overlap)]
+    Ds = [np.zeros(n, F64) for _ in range(overlap)]
     losses = []
     boundaries = 0
     for t in range(1, H * phases + 1):
@@ -276,9 +283,14 @@ def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
                 losses.append(quadratic_loss(a, h, theta_star))
             else:
                 step = outer_eager if variant == "eager" else outer_delayed
-                step(theta, a, u, P, D, eta, mu, nesterov, apply_update=(boundaries > 1))
+                slot = boundaries % overlap
+                step(theta, a, u, Ps[slot], Ds[slot], eta, mu, nesterov,
+                     apply_update=(boundaries > overlap))
                 losses.append(quadratic_loss(mean_over_replicas(a), h, theta_star))
-    return dict(theta=theta, a=a, u=u, P=P, D=D, m1=m1, m2=m2), losses
+    out = dict(theta=theta, a=a, u=u, P=Ps[0], D=Ds[0], m1=m1, m2=m2)
+    if overlap > 1:
+        out.update(Ps=Ps, Ds=Ds)
+    return out, losses
 
 
 def run_streaming_quadratic(variant, fragments, M, H, phases, h, theta_star, seed, noise_std,

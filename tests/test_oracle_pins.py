@@ -499,3 +499,65 @@ def test_full_precision_communication_is_the_default():
     O.outer_eager(*s2, 0.7, 0.9, True, True, comm="f32")
     for x, y in zip(s1, s2):
         np.testing.assert_array_equal(x, y)
+
+
+# ------------------------------------------------ two-outer-steps overlap ---
+def test_two_step_overlap_by_brute_force_with_full_history():
+    """The reading of the 2-outer-steps overlap (no formula in the paper): at boundary b > 2 every
+    replica feeds (Delta_m^(b) + sum_{m' != m} Delta_m'^(b-2)) / M.  Recomputed with the complete
+    history of outer gradients in Python lists and one torch SGD per replica; the inner phase is
+    the noise-free quadratic so both sides can run it."""
+    M, n, H, phases = 3, 5, 3, 6
+    lr, b1, b2, eps, eta, mu = 2e-2, 0.9, 0.95, 1e-8, 0.7, 0.9
+    h = np.exp(RNG.uniform(np.log(1e-3), 0.0, n))
+    star = rnd(n)
+    st, _ = O.run_quadratic("eager", M, H, phases, h, star, seed=4, noise_std=0.1, lr=lr, beta1=b1,
+                            beta2=b2, eps=eps, weight_decay=0.0, eta=eta, mu=mu, overlap=2)
+    theta = np.zeros((M, n))
+    m1, m2 = np.zeros((M, n)), np.zeros((M, n))
+    ps, opts = _torch_replicas(np.zeros(n), M, eta, mu)
+    anchors = [np.zeros(n) for _ in range(M)]
+    history = []                      # history[b-1][m] = Delta_m at boundary b
+    for t in range(1, H * phases + 1):
+        O.quadratic_inner_step(theta, m1, m2, h, star, t, 4, 0.1, lr, b1, b2, eps, 0.0)
+        if t % H:
+            continue
+        b = t // H
+        now = [anchors[m] - theta[m] for m in range(M)]
+        if b > 2:
+            old = history[b - 3]
+            for m in range(M):
+                g = (now[m] + sum(old[q] for q in range(M) if q != m)) / M
+                ps[m].grad = torch.tensor(g)
+                opts[m].step()
+                anchors[m] = ps[m].detach().numpy().copy()
+        else:
+            for m in range(M):
+                anchors[m] = theta[m].copy()
+                with torch.no_grad():
+                    ps[m].copy_(torch.tensor(theta[m]))
+        history.append(now)
+        for m in range(M):
+            theta[m] = anchors[m]
+    np.testing.assert_allclose(st["a"], np.array(anchors), rtol=1e-9, atol=1e-14)
+    np.testing.assert_allclose(st["theta"], theta, rtol=1e-9, atol=1e-14)
+    # the two slots hold the last two generations
+    last, before = history[-1], history[-2]
+    slot_last = phases % 2
+    np.testing.assert_allclose(st["Ps"][slot_last], np.array(last), rtol=1e-9, atol=1e-14)
+    np.testing.assert_allclose(st["Ps"][1 - slot_last], np.array(before), rtol=1e-9, atol=1e-14)
+    np.testing.assert_allclose(st["Ds"][slot_last], np.mean(np.array(last), axis=0), rtol=1e-9, atol=1e-14)
+
+
+def test_overlap_one_is_the_listing():
+    n = 6
+    h = np.exp(RNG.uniform(np.log(1e-3), 0.0, n))
+    star = rnd(n)
+    kw = dict(M=2, H=3, phases=4, h=h, theta_star=star, seed=9, noise_std=0.1, lr=1e-2, beta1=0.9,
+              beta2=0.95, eps=1e-8, weight_decay=0.0, eta=0.7, mu=0.9)
+    s1, l1 = O.run_quadratic("eager", **kw)
+    s2, l2 = O.run_quadratic("eager", overlap=1, **kw)
+    for k in s1:
+        np.testing.assert_array_equal(s1[k], s2[k])
+    s3, _ = O.run_quadratic("eager", overlap=2, **kw)
+    assert np.max(np.abs(s3["a"] - s1["a"])) > 0

@@ -132,3 +132,38 @@ def test_staggered_run_through_window_calls(variant):
             # trajectory mode (measured 5e-6), not the per-call 1e-6 gate
             worst = max(worst, assert_close(W.to_f64(g), want, 2e-5, f"{variant} fragment at {off} {name}"))
     print(f"streaming/{variant}: worst trajectory error {worst:.2e}")
+
+
+@pytest.mark.gpu
+def test_two_outer_steps_overlap_through_alternating_state_slots():
+    """2-outer-steps eager overlap (Section 3.2; no formula in the paper, so parity is only
+    against this build's reading): the previous-gradient buffers of two generations are used
+    alternately, the kernels are the ordinary eager ones."""
+    DEV = "cuda:0"
+    M, n, H, phases = 4, 20_003, 5, 7
+    q = QUAD
+    h = W.log_uniform((n,), 1e-3, 1.0, tag="h", seed=67, device=DEV)
+    star = W.normal((n,), 1.0, tag="theta_star", seed=67, device=DEV)
+    ns = (n + 3) & ~3
+    theta = torch.zeros((M, ns), device=DEV)
+    m1, m2 = torch.zeros_like(theta), torch.zeros_like(theta)
+    a, u = torch.zeros((M, ns), device=DEV), torch.zeros((M, ns), device=DEV)
+    Ps = [torch.zeros((M, ns), device=DEV) for _ in range(2)]
+    Ds = [torch.zeros(n, device=DEV) for _ in range(2)]
+    for t in range(1, H * phases + 1):
+        d.sim_quadratic_inner(theta, m1, m2, h, star, n=n, noise_std=q["noise_std"], seed=q["seed"],
+                              lr=q["lr"], beta1=q["beta1"], beta2=q["beta2"], eps=q["eps"],
+                              weight_decay=0.0, step=t)
+        if t % H == 0:
+            b = t // H
+            d.outer_eager(theta, a, u, Ps[b % 2], Ds[b % 2], n=n, outer_lr=q["eta"],
+                          outer_momentum=q["mu"], apply_update=(b > 2))
+    torch.cuda.synchronize()
+    ref, _ = O.run_quadratic("eager", M, H, phases, W.to_f64(h), W.to_f64(star), q["seed"],
+                             q["noise_std"], q["lr"], q["beta1"], q["beta2"], q["eps"], 0.0,
+                             q["eta"], q["mu"], overlap=2)
+    for name, g, want in (("theta", theta, ref["theta"]), ("anchor", a, ref["a"]), ("vel", u, ref["u"]),
+                          ("P0", Ps[0], ref["Ps"][0]), ("P1", Ps[1], ref["Ps"][1])):
+        assert_close(W.to_f64(g[:, :n]), want, 2e-5, f"2-step overlap {name}")
+    for k in range(2):
+        assert_close(W.to_f64(Ds[k]), ref["Ds"][k], 2e-5, f"2-step overlap D{k}")
