@@ -63,7 +63,8 @@ int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream
 /*
  * Launch tuning for measurements.  Keys: "block" (threads per workgroup: 64..512,
  * power of two), "xcd_remap" (0/1: give each of the 8 XCDs a contiguous slice of the
- * index space).
+ * index space), "generic_path" (eager kernel for replica counts without a register
+ * instantiation: 0 = choose, 1 = LDS-staged, 2 = two-pass).
  * Returns DILOCO_OK or DILOCO_ERR_HYPER for an unknown key / value.  Not thread safe.
  */
 int diloco_tune(const char* key, int value);

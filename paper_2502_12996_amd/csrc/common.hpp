@@ -78,6 +78,7 @@ __device__ __forceinline__ int64_t logical_block(int64_t per_xcd) {
 struct Tuning {
     int block = 256;
     int xcd_remap = 0;
+    int generic_path = 0;  // eager kernel for M without a register instantiation: 0 auto, 1 LDS, 2 two-pass
 };
 Tuning& tuning();
 

@@ -38,6 +38,8 @@ __device__ __forceinline__ f4 sent(f4 d, const OuterScalars& sc) {
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
+constexpr int kLdsPerCu = 160 * 1024;  // gfx950
+constexpr int kMinStagedWaves = 6;     // LDS path only while this many wavefronts fit a CU
 constexpr int kTileShift = 12;  // DILOCO_STATE_TILE = 4096 elements
 constexpr int64_t kTile = (int64_t)1 << kTileShift;
 static_assert(kTile == DILOCO_STATE_TILE, "header and kernels disagree on the state tile");
@@ -242,6 +244,54 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restri
     store4(sv.d(i), dbar);
 }
 
+// ------------------------------------------------------------------ two-pass vector path
+// Any M, no staging: the second loop re-reads theta_m and a_m (2 of the 8M+2 accesses per
+// index are read twice).  Keeps full occupancy when M is too large for the LDS path to leave
+// enough wavefronts per CU.
+template <typename TT, int MODE, typename SV>
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_twopass_kernel(TT* __restrict__ theta, SV sv, int M,
+                                                                        int64_t n, int64_t stride,
+                                                                        OuterScalars sc, int64_t per_xcd) {
+    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    const int64_t nvec = n >> 2;
+    if (v >= nvec) {
+        if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, M, n, stride, sc);
+        return;
+    }
+    const int64_t i = v << 2;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll 4
+    for (int m = 0; m < M; ++m) {
+        const f4 q = sent(load4(sv.a(m, i)) - load4(theta + m * stride + i), sc);
+        s0 += (double)q.x;
+        s1 += (double)q.y;
+        s2 += (double)q.z;
+        s3 += (double)q.w;
+    }
+    f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
+               (float)(s3 * sc.inv_M_d)};
+    f4 Dold = {0.f, 0.f, 0.f, 0.f};
+    if (MODE != MODE_RECORD) Dold = load4(sv.d(i));
+    for (int m = 0; m < M; ++m) {
+        f4 an = load4(sv.a(m, i));
+        const f4 th = load4(theta + m * stride + i);
+        const f4 d = an - th;
+        if (MODE == MODE_RECORD) {
+            store4(sv.a(m, i), th);
+        } else {
+            f4 un = load4(sv.u(m, i));
+            f4 G = Dold;
+            if (MODE == MODE_EAGER) G = eager_gradient(d, load4(sv.p(m, i)), Dold, sc);
+            outer_opt(an, un, G, sc);
+            store4(theta + m * stride + i, an);
+            store4(sv.a(m, i), an);
+            store4(sv.u(m, i), un);
+        }
+        store4(sv.p(m, i), sent(d, sc));
+    }
+    store4(sv.d(i), dbar);
+}
+
 // ------------------------------------------------------------------ standard DiLoCo
 // Shared outer parameters: nothing per replica has to survive the reduction, so a runtime
 // loop over m suffices.
@@ -419,29 +469,23 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
         default: break;
     }
 #undef DILOCO_REG_CASE
-    // LDS staging: 32 bytes per thread and replica; shrink the workgroup until it fits.
-    int dev = 0, lds_max = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
-        return DILOCO_ERR_LAUNCH;
-    int b = block;
-    while (b > 64 && (int64_t)b * 32 * M > lds_max) b >>= 1;
-    const int64_t lds = (int64_t)b * 32 * M;
-    if (lds <= lds_max) {
+    // Other M.  LDS staging (32 bytes per thread and replica, one wavefront per workgroup) while
+    // at least kMinStagedWaves such workgroups fit a CU's 160 KB; beyond that the two-pass kernel.
+    const int64_t lds = (int64_t)64 * 32 * M;
+    const int path = tuning().generic_path;  // 0: choose, 1: LDS, 2: two-pass
+    if ((path == 0 && lds * kMinStagedWaves <= kLdsPerCu) || (path == 1 && lds <= kLdsPerCu)) {
         if (lds > 48 * 1024 &&
             hipFuncSetAttribute(reinterpret_cast<const void*>(&outer_eager_lds_kernel<TT, MODE, SV>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return DILOCO_ERR_LAUNCH;
-        Grid g = make_grid(threads, b);
-        hipLaunchKernelGGL((outer_eager_lds_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(b), (size_t)lds, st,
+        Grid g = make_grid(threads, 64);
+        hipLaunchKernelGGL((outer_eager_lds_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(64), (size_t)lds, st,
                            theta, sv, M, n, stride, sc, g.per_xcd);
         return launch_status();
     }
-    // M too large even for one wavefront per workgroup: element-wise two-pass kernel.
-    if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(n, block);
-    hipLaunchKernelGGL((outer_eager_scalar_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(block), 0, st, theta, sv,
-                       M, n, stride, sc, g.per_xcd);
+    Grid g = make_grid(threads, block);
+    hipLaunchKernelGGL((outer_eager_twopass_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(block), 0, st, theta,
+                       sv, M, n, stride, sc, g.per_xcd);
     return launch_status();
 }
 

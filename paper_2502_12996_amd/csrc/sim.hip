@@ -153,6 +153,11 @@ extern "C" int diloco_tune(const char* key, int value) {
         tuning().xcd_remap = value;
         return DILOCO_OK;
     }
+    if (!std::strcmp(key, "generic_path")) {
+        if (value < 0 || value > 2) return DILOCO_ERR_HYPER;
+        tuning().generic_path = value;
+        return DILOCO_OK;
+    }
     return DILOCO_ERR_HYPER;
 }
 
@@ -160,6 +165,7 @@ extern "C" int diloco_tune_get(const char* key) {
     if (!key) return -1;
     if (!std::strcmp(key, "block")) return tuning().block;
     if (!std::strcmp(key, "xcd_remap")) return tuning().xcd_remap;
+    if (!std::strcmp(key, "generic_path")) return tuning().generic_path;
     return -1;
 }
 

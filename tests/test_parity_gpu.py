@@ -108,6 +108,32 @@ def test_eager_large_M_paths_agree_bitwise():
         assert torch.equal(a[k][..., :n], b[k][..., :n]), k
 
 
+@pytest.mark.parametrize("M", [5, 12, 16, 40])
+def test_eager_generic_paths_agree_bitwise(M):
+    """Replica counts without a register instantiation run LDS-staged or two-pass; both promise
+    the arithmetic of the register kernel in the same order."""
+    n = 20_003
+    out = []
+    for path in (1, 2):
+        d.tune("generic_path", path)
+        try:
+            g = _rows(M, n, 71)
+            d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"],
+                          outer_lr=ETA, outer_momentum=MU)
+            torch.cuda.synchronize()
+            out.append(g)
+        finally:
+            d.tune("generic_path", 0)
+    for k in out[0]:
+        assert torch.equal(out[0][k], out[1][k]), k
+    st = W.outer_state(wl_for(M, n), n, seed=71)
+    ref = {k: W.to_f64(v) for k, v in st.items()}
+    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU,
+                  True, True)
+    for k in ref:
+        assert_close(W.to_f64(out[1][k]), ref[k], TOL_F32, f"two-pass M={M} {k}")
+
+
 def test_eager_empty_input_is_a_noop():
     wl = wl_for(2, 8)
     g = {k: v.to(DEV) for k, v in W.outer_state(wl, 8, seed=2).items()}
