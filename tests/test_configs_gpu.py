@@ -198,7 +198,8 @@ def test_full_size_eager_outer_step_per_call(name):
     s = st["prev_local"][0].double()
     for m in range(1, M):
         s += st["prev_local"][m].double()
-    assert torch.equal((s / M).float(), st["prev_mean"])     # the stored mean is the mean of the stored locals
+    # the stored mean is the mean of the stored locals (M is a power of two here: exact division)
+    assert torch.equal((s / M).float(), st["prev_mean"])
     print(f"{name}: worst per-call error / tolerance {worst:.3f}")
     del st, s
     torch.cuda.empty_cache()
@@ -299,8 +300,9 @@ def test_quadratic_forty_phases(variant, lr_div):
           f"loss deviation {worst_loss:.2e}, worst state error after {H * wl.phases} steps {worst_state:.2e}")
 
 
-def test_t550m_packed_state_eager_outer_step_per_call():
-    """Config 3 through the packed-state entry point, the launch the benchmark times."""
+@pytest.mark.parametrize("block,xcd", [(256, 0), (64, 1), (512, 1)])
+def test_t550m_packed_state_eager_outer_step_per_call(block, xcd):
+    """Config 3 through the packed-state entry point, in launch shapes the benchmark picks from."""
     wl = W.WORKLOADS["t550m"]
     M, n = wl.M, wl.n
     st = W.outer_state(wl, n, device=DEV)
@@ -311,7 +313,13 @@ def test_t550m_packed_state_eager_outer_step_per_call():
                  prev_mean=st["prev_mean"])
     for k in ("anchor", "vel", "prev_local", "prev_mean"):
         st[k].zero_()
-    d.outer_eager_packed(st["theta"], state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
+    d.tune("block", block)
+    d.tune("xcd_remap", xcd)
+    try:
+        d.outer_eager_packed(st["theta"], state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
+    finally:
+        d.tune("block", 256)
+        d.tune("xcd_remap", 0)
     d.unpack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
                    prev_mean=st["prev_mean"])
     torch.cuda.synchronize()
@@ -322,6 +330,10 @@ def test_t550m_packed_state_eager_outer_step_per_call():
         for k in r:
             worst = max(worst, assert_close(f64(st[k][..., lo:hi]), r[k], TOL_F32, f"packed {k} [{lo},{hi})"))
     assert torch.equal(st["theta"], st["anchor"])
-    print(f"t550m packed: worst per-call error {worst:.2e}")
-    del st, state
+    s = st["prev_local"][0].double()
+    for m in range(1, M):
+        s += st["prev_local"][m].double()
+    assert torch.equal((s / M).float(), st["prev_mean"])     # M is a power of two: the division is exact
+    print(f"t550m packed, block={block} xcd_remap={xcd}: worst per-call error {worst:.2e}")
+    del st, state, s
     torch.cuda.empty_cache()

@@ -432,3 +432,65 @@ def test_unknown_variant_bits_are_rejected():
         d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"],
                       outer_lr=ETA, outer_momentum=MU, variant=0x200)
     assert ei.value.status == d.binding.ERR_DTYPE
+
+
+# ------------------------------------------------------------------ launch shapes the benchmark may pick
+@pytest.fixture
+def launch_shape(request):
+    block, xcd = request.param
+    d.tune("block", block)
+    d.tune("xcd_remap", xcd)
+    yield block, xcd
+    d.tune("block", 256)
+    d.tune("xcd_remap", 0)
+
+
+@pytest.mark.parametrize("launch_shape", [(64, 0), (64, 1), (128, 1), (256, 1), (512, 0), (512, 1)], indirect=True)
+def test_every_launch_shape_gives_the_same_bits(launch_shape):
+    """Workgroup size and XCD-contiguous workgroup order only change who computes what."""
+    M, n = 8, 150_003                     # > 32 workgroups at every size, ragged tail
+    # eager, rows and packed, against the default shape
+    want = _rows(M, n, 73)
+    got = _rows(M, n, 73)
+    pk = _rows(M, n, 73)
+    block, xcd = launch_shape
+    d.tune("block", 256); d.tune("xcd_remap", 0)
+    d.outer_eager(want["theta"], want["anchor"], want["vel"], want["prev_local"], want["prev_mean"],
+                  outer_lr=ETA, outer_momentum=MU)
+    d.tune("block", block); d.tune("xcd_remap", xcd)
+    d.outer_eager(got["theta"], got["anchor"], got["vel"], got["prev_local"], got["prev_mean"],
+                  outer_lr=ETA, outer_momentum=MU)
+    state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+    d.pack_state(state, M, n, anchor=pk["anchor"], vel=pk["vel"], prev_local=pk["prev_local"],
+                 prev_mean=pk["prev_mean"])
+    d.outer_eager_packed(pk["theta"], state, outer_lr=ETA, outer_momentum=MU)
+    d.unpack_state(state, M, n, anchor=pk["anchor"], vel=pk["vel"], prev_local=pk["prev_local"],
+                   prev_mean=pk["prev_mean"])
+    torch.cuda.synchronize()
+    for k in want:
+        assert torch.equal(want[k], got[k]), k
+        assert torch.equal(want[k], pk[k]), k
+    # AdamW, standard outer step, reset, quadratic step: against the checker
+    wl = wl_for(3, n)
+    ad = W.adamw_state(wl, n, seed=79)
+    ref = {k: W.to_f64(v) for k, v in ad.items()}
+    O.adamw_step(ref["theta"], ref["m1"], ref["m2"], ref["grad"], 5, wl.lr, wl.beta1, wl.beta2, wl.eps,
+                 wl.weight_decay)
+    g = {k: v.to(DEV) for k, v in ad.items()}
+    d.inner_adamw(g["theta"], g["m1"], g["m2"], g["grad"], lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2,
+                  eps=wl.eps, weight_decay=wl.weight_decay, step=5)
+    torch.cuda.synchronize()
+    for k in ("theta", "m1", "m2"):
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"adamw {k} at shape {launch_shape}")
+    st = W.outer_state(wl, n, seed=83)
+    theta, a, u = st["theta"], st["anchor"][0].clone(), st["vel"][0].clone()
+    rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
+    O.outer_standard(rt, ra, ru, ETA, MU, True)
+    gt, ga, gu = theta.to(DEV), a.to(DEV), u.to(DEV)
+    d.outer_sync(gt, ga, gu, outer_lr=ETA, outer_momentum=MU)
+    th2 = torch.zeros_like(gt)
+    d.reset(th2, ga)
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(ga), ra, TOL_F32, "sync anchor")
+    assert_close(W.to_f64(gu), ru, TOL_F32, "sync vel")
+    assert torch.equal(gt, ga.expand(3, n)) and torch.equal(th2, gt)
