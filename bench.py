@@ -218,11 +218,10 @@ def main():
     if packed and wl.layers:
         set_shape(shape_outer)
         frs = W.fragments(wl.layers, wl.d_model, wl.vocab)
-        S = 3 * M + 1
 
         def run_fragments():
             for off, cnt in frs:
-                d.outer_eager_packed(theta[:, off:off + cnt], state[(off // 4096) * S * 4096:], n=cnt, **okw)
+                d.outer_eager_packed(theta[:, off:off + cnt], d.packed_window(state, M, off), n=cnt, **okw)
         run_fragments()
         fms = timed(run_fragments, 5)[2]
         extra["outer_step_by_fragments"] = {"fragments": len(frs), "ms": fms,

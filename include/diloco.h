@@ -142,15 +142,16 @@ int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, int64_t n, 
  * gigabytes apart, and a wavefront's 3M+1 accesses land in 3M+1 different pages.  The
  * packed form is one buffer of diloco_packed_state_elems(M, n) floats laid out
  * [tile][3M+1][DILOCO_STATE_TILE]: tile t holds, for parameter indices
- * [t*4096, (t+1)*4096), stream 3m = outer parameters of replica m, 3m+1 = its velocity,
- * 3m+2 = its previous local outer gradient, stream 3M = the previous mean.  The last
- * tile is padded.  A window [off, off+n) of a larger model may be swept on its own when
- * off is a multiple of DILOCO_STATE_TILE: pass state + (off/4096)*(3M+1)*4096.
+ * [t*8192, (t+1)*8192), in the order the kernel touches them: streams 0..M-1 = outer
+ * parameters of replicas 0..M-1, stream M = the previous mean, stream M+1+2m = velocity of
+ * replica m, stream M+2+2m = its previous local outer gradient.  The last tile is padded.
+ * A window [off, off+n) of a larger model may be swept on its own when off is a multiple
+ * of DILOCO_STATE_TILE: pass state + (off/8192)*(3M+1)*8192.
  * diloco_outer_eager_packed computes exactly what diloco_outer_eager computes (same
  * arithmetic, same order, bit-identical results); only the addresses differ.
  * state must be 16-byte aligned.
  */
-#define DILOCO_STATE_TILE 4096
+#define DILOCO_STATE_TILE 8192
 
 /* Floats in the packed state of M replicas x n parameters; -1 for invalid M or n. */
 int64_t diloco_packed_state_elems(int M, int64_t n);

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libdiloco.so")
 F32, BF16 = 0, 1
 EAGER, DELAYED = 0, 1
 COMM_BF16 = 0x100   # OR into `variant`: outer gradients cross the wire in bf16
+STATE_TILE = 8192    # DILOCO_STATE_TILE: elements per stream and tile of the packed outer state
 
 OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_HYPER, ERR_ALIAS, ERR_LAUNCH = range(8)
 
@@ -171,6 +172,12 @@ def _state_stride(M, n, *rows):
             assert ss is None or ss == s, "anchor, vel and prev_local must share one row stride"
             ss = s
     return n if ss is None else ss
+
+
+def packed_window(state, M: int, offset: int):
+    """View of the packed state that starts at parameter index `offset` (a multiple of STATE_TILE)."""
+    assert offset % STATE_TILE == 0, "packed-state windows start at tile boundaries"
+    return state[(offset // STATE_TILE) * (3 * M + 1) * STATE_TILE:]
 
 
 def pack_state(state, M, n, *, anchor=None, vel=None, prev_local=None, prev_mean=None,

@@ -11,8 +11,9 @@
 // The per-replica outer state (outer parameters a_m, velocity u_m, previous local outer
 // gradient P_m) and the previous mean D are reached through a "state view":
 //   RowState    the caller's [M][state_stride] rows and [n] mean;
-//   TiledState  one library-defined buffer [tile][3M+1][4096 elements]: the 3M+1 state
-//               streams of 4096 consecutive parameters sit next to each other, so a
+//   TiledState  one library-defined buffer [tile][3M+1][8192 elements]: the 3M+1 state
+//               streams of 8192 consecutive parameters sit next to each other, in the order
+//               the kernel touches them (a_0..a_{M-1}, D, u_0, P_0, u_1, P_1, ...), so a
 //               wavefront's 3M+1 state accesses fall into one or two 2 MB pages instead of
 //               3M+1 pages that are gigabytes apart (fewer address-translation misses).
 #include "common.hpp"
@@ -40,7 +41,7 @@ enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
 constexpr int kLdsPerCu = 160 * 1024;  // gfx950
 constexpr int kMinStagedWaves = 6;     // LDS path only while this many wavefronts fit a CU
-constexpr int kTileShift = 12;  // DILOCO_STATE_TILE = 4096 elements
+constexpr int kTileShift = 13;  // DILOCO_STATE_TILE = 8192 elements
 constexpr int64_t kTile = (int64_t)1 << kTileShift;
 static_assert(kTile == DILOCO_STATE_TILE, "header and kernels disagree on the state tile");
 
@@ -58,14 +59,14 @@ struct RowState {
 
 struct TiledState {
     float* base;
-    int64_t S;  // streams per tile: 3M + 1
+    int64_t M;  // replicas; streams per tile: 3M + 1
     __device__ __forceinline__ float* at(int64_t s, int64_t i) const {
-        return base + ((((i >> kTileShift) * S + s) << kTileShift) | (i & (kTile - 1)));
+        return base + ((((i >> kTileShift) * (3 * M + 1) + s) << kTileShift) | (i & (kTile - 1)));
     }
-    __device__ __forceinline__ float* a(int m, int64_t i) const { return at(3 * m, i); }
-    __device__ __forceinline__ float* u(int m, int64_t i) const { return at(3 * m + 1, i); }
-    __device__ __forceinline__ float* p(int m, int64_t i) const { return at(3 * m + 2, i); }
-    __device__ __forceinline__ float* d(int64_t i) const { return at(S - 1, i); }
+    __device__ __forceinline__ float* a(int m, int64_t i) const { return at(m, i); }
+    __device__ __forceinline__ float* d(int64_t i) const { return at(M, i); }
+    __device__ __forceinline__ float* u(int m, int64_t i) const { return at(M + 1 + 2 * m, i); }
+    __device__ __forceinline__ float* p(int m, int64_t i) const { return at(M + 2 + 2 * m, i); }
 };
 
 // OuterOpt on one value (or 4): u <- mu u + G ; a <- a - (c_g G + c_u u).
@@ -364,9 +365,9 @@ struct RowAnchor {
 };
 struct TiledAnchor {
     const float* base;
-    int64_t S;
+    int64_t S;  // streams per tile: 3M + 1
     __device__ __forceinline__ const float* a(int m, int64_t i) const {
-        return base + ((((i >> kTileShift) * S + 3 * m) << kTileShift) | (i & (kTile - 1)));
+        return base + ((((i >> kTileShift) * S + m) << kTileShift) | (i & (kTile - 1)));
     }
 };
 
@@ -393,7 +394,7 @@ __global__ __launch_bounds__(kMaxBlock) void reset_scalar_kernel(TT* theta, AV a
 }
 
 // ------------------------------------------------------------------ rows <-> tiled state
-// grid.y = state stream s (3m: a_m, 3m+1: u_m, 3m+2: P_m, 3M: D).  TO_TILED: rows -> tiled.
+// grid.y = state stream s (m < M: a_m; M: D; M+1+2m: u_m; M+2+2m: P_m).  TO_TILED: rows -> tiled.
 // A NULL row buffer skips its streams.  VEC = 4 or 1.
 template <bool TO_TILED, int VEC>
 __global__ __launch_bounds__(kMaxBlock) void repack_kernel(float* tiled, float* anchor, float* vel, float* P,
@@ -404,11 +405,13 @@ __global__ __launch_bounds__(kMaxBlock) void repack_kernel(float* tiled, float* 
     const int s = blockIdx.y;
     const int64_t S = 3 * M + 1;
     float* row;
-    if (s == 3 * M) {
+    if (s < M) {
+        row = anchor ? anchor + s * ss : nullptr;
+    } else if (s == M) {
         row = D;
     } else {
-        const int m = s / 3, k = s - 3 * m;
-        float* b = k == 0 ? anchor : (k == 1 ? vel : P);
+        const int k = s - M - 1, m = k >> 1;
+        float* b = (k & 1) ? P : vel;
         row = b ? b + m * ss : nullptr;
     }
     if (!row) return;
@@ -569,7 +572,7 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
     const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov, comm_bf16);
-    const TiledState sv{state, 3 * (int64_t)M + 1};
+    const TiledState sv{state, (int64_t)M};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)
         return dispatch_eager<float, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);

@@ -122,7 +122,9 @@ def test_reset_validation(lib):
 
 
 def test_packed_state_validation(lib):
-    assert lib.diloco_packed_state_elems(8, 4097) == 2 * 25 * 4096
+    tile = int(re.search(r"#define DILOCO_STATE_TILE (\d+)", open(os.path.join(ROOT, "include", "diloco.h")).read()).group(1))
+    assert tile == B.STATE_TILE
+    assert lib.diloco_packed_state_elems(8, tile + 1) == 2 * 25 * tile
     assert lib.diloco_packed_state_elems(1, 0) == 0
     assert lib.diloco_packed_state_elems(0, 5) == -1
     assert lib.diloco_packed_state_elems(2, -1) == -1

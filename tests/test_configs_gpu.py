@@ -306,7 +306,7 @@ def test_t550m_packed_state_eager_outer_step_per_call(block, xcd):
     wl = W.WORKLOADS["t550m"]
     M, n = wl.M, wl.n
     st = W.outer_state(wl, n, device=DEV)
-    chunks = big_chunks(n) + [(4096 * 1000 - 100, 4096 * 1000 + 100)]     # straddles a tile boundary
+    chunks = big_chunks(n) + [(d.STATE_TILE * 1000 - 100, d.STATE_TILE * 1000 + 100)]   # straddles a tile boundary
     ref = [{k: f64(v[..., lo:hi]) for k, v in st.items()} for (lo, hi) in chunks]
     state = torch.empty(d.packed_state_elems(M, n), device=DEV)
     d.pack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],

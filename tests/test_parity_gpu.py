@@ -303,23 +303,23 @@ def _rows(M, n, seed, bf16=False, pad=0):
 
 
 @pytest.mark.parametrize("M", [1, 3, 8])
-@pytest.mark.parametrize("n,pad", [(1, 0), (4095, 1), (4096, 0), (4097, 3), (3 * 4096 + 5, 2), (70_003, 1)])
+@pytest.mark.parametrize("n,pad", [(1, 0), (8191, 1), (8192, 0), (8193, 3), (3 * 8192 + 5, 2), (70_003, 1)])
 def test_pack_unpack_roundtrip_and_layout(M, n, pad):
     g = _rows(M, n, 41, pad=pad)
     state = torch.full((d.packed_state_elems(M, n),), -7.0, device=DEV)
     d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
                  prev_mean=g["prev_mean"])
     torch.cuda.synchronize()
-    # the documented layout: [tile][3M+1][4096]
-    S, T = 3 * M + 1, 4096
+    # the documented layout: [tile][a_0..a_{M-1}, D, u_0, P_0, u_1, P_1, ...][STATE_TILE]
+    S, T = 3 * M + 1, d.STATE_TILE
     tiles = (n + T - 1) // T
     v = state.view(tiles, S, T).cpu()
     for m in range(M):
-        for k, name in enumerate(("anchor", "vel", "prev_local")):
+        for pos, name in ((m, "anchor"), (M + 1 + 2 * m, "vel"), (M + 2 + 2 * m, "prev_local")):
             rows = g[name][m, :n].cpu()
-            got = v[:, 3 * m + k, :].reshape(-1)[:n]
+            got = v[:, pos, :].reshape(-1)[:n]
             assert torch.equal(got, rows), (m, name)
-    assert torch.equal(v[:, 3 * M, :].reshape(-1)[:n], g["prev_mean"].cpu())
+    assert torch.equal(v[:, M, :].reshape(-1)[:n], g["prev_mean"].cpu())
     assert (v.reshape(tiles, S, T)[-1, :, n - (tiles - 1) * T:] == -7.0).all()   # padding untouched
     out = {k: torch.zeros_like(x) for k, x in g.items() if k != "theta"}
     d.unpack_state(state, M, n, anchor=out["anchor"], vel=out["vel"], prev_local=out["prev_local"],
@@ -335,11 +335,11 @@ def test_pack_unpack_roundtrip_and_layout(M, n, pad):
     torch.cuda.synchronize()
     v2 = state.view(tiles, S, T).cpu()
     assert torch.equal(v2[:, 0, :].reshape(-1)[:n], g["vel"][0, :n].cpu())
-    assert torch.equal(v2[:, 1, :], before.view(tiles, S, T)[:, 1, :].cpu())
+    assert torch.equal(v2[:, M, :], before.view(tiles, S, T)[:, M, :].cpu())
 
 
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 8, 5, 16, 33])
-@pytest.mark.parametrize("n", [1, 5, 4095, 4097, 70_003])
+@pytest.mark.parametrize("n", [1, 5, 8191, 8193, 70_003])
 @pytest.mark.parametrize("variant,apply", [("eager", True), ("delayed", True), ("eager", False)])
 def test_eager_packed_is_bit_identical_to_rows(M, n, variant, apply):
     bf16 = (M + n) % 2 == 0
@@ -379,7 +379,7 @@ def test_eager_packed_against_the_checker_and_elementwise_path():
 
 
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("n,pad", [(5, 0), (4097, 0), (20_001, 1)])
+@pytest.mark.parametrize("n,pad", [(5, 0), (8193, 0), (20_001, 1)])
 def test_reset_packed(bf16, n, pad):
     M = 3
     g = _rows(M, n, 53, bf16, pad=pad)

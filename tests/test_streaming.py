@@ -82,7 +82,7 @@ def test_staggered_run_through_window_calls(variant):
     n = W.transformer_param_count(L, dm, V)
     frags = W.fragments(L, dm, V)
     F = len(frags)
-    assert F == 2 and all(off % 4096 == 0 for off, _ in frags)
+    assert F == 2 and all(off % d.STATE_TILE == 0 for off, _ in frags)
     h = W.log_uniform((n,), 1e-3, 1.0, tag="h", seed=61, device=DEV)
     star = W.normal((n,), 1.0, tag="theta_star", seed=61, device=DEV)
     theta = torch.zeros((M, n), device=DEV)
@@ -92,7 +92,6 @@ def test_staggered_run_through_window_calls(variant):
     u = torch.zeros_like(a)
     P = torch.zeros((M, n), device=DEV)
     D = torch.zeros(n, device=DEV)
-    S = 3 * M + 1
     state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
     q = QUAD
     for t in range(1, H * phases + 1):
@@ -108,7 +107,7 @@ def test_staggered_run_through_window_calls(variant):
             if shared:
                 d.outer_sync(th, a[off:off + cnt], u[off:off + cnt], **kw)
             elif variant == "eager_packed":
-                d.outer_eager_packed(th, state[(off // 4096) * S * 4096:], apply_update=apply, **kw)
+                d.outer_eager_packed(th, d.packed_window(state, M, off), apply_update=apply, **kw)
             else:
                 d.outer_eager(th, a[:, off:off + cnt], u[:, off:off + cnt], P[:, off:off + cnt],
                               D[off:off + cnt], apply_update=apply,
