@@ -166,3 +166,26 @@ def test_two_outer_steps_overlap_through_alternating_state_slots():
         assert_close(W.to_f64(g[:, :n]), want, 2e-5, f"2-step overlap {name}")
     for k in range(2):
         assert_close(W.to_f64(Ds[k]), ref["Ds"][k], 2e-5, f"2-step overlap D{k}")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant,layout,overlap", [("standard", "rows", 1), ("eager", "packed", 1),
+                                                    ("eager", "rows", 1), ("delayed", "packed", 1),
+                                                    ("eager", "rows", 2)])
+def test_simulation_driver_matches_the_checker(variant, layout, overlap):
+    from paper_2502_12996_amd.simulate import QuadraticSimulation
+    M, n, H, phases = 3, 20_003, 4, 5
+    q = QUAD
+    sim = QuadraticSimulation(M, n, H, variant, layout=layout, overlap=overlap, seed=q["seed"],
+                              noise_std=q["noise_std"], lr=q["lr"], beta1=q["beta1"], beta2=q["beta2"],
+                              eps=q["eps"], weight_decay=0.0, outer_lr=q["eta"], outer_momentum=q["mu"])
+    losses = sim.run(phases)
+    ref, ref_losses = O.run_quadratic(variant, M, H, phases, W.to_f64(sim.h), W.to_f64(sim.star),
+                                      q["seed"], q["noise_std"], q["lr"], q["beta1"], q["beta2"],
+                                      q["eps"], 0.0, q["eta"], q["mu"], overlap=overlap)
+    assert len(losses) == phases
+    np.testing.assert_allclose(losses, ref_losses, rtol=1e-5)
+    a = sim.outer_parameters()
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(a if variant == "standard" else a[:, :n]), ref["a"], 2e-5, "outer parameters")
+    assert_close(W.to_f64(sim.theta[:, :n]), ref["theta"], 2e-5, "theta")
