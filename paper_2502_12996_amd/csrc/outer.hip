@@ -174,22 +174,34 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
     }
     f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
                (float)(s3 * sc.inv_M_d)};
+    // Stores leave in address order: the theta rows, then the state streams as the packed
+    // layout holds them (a_0..a_{M-1}, D, u_0, P_0, u_1, ...).  Against stores interleaved per
+    // replica this measured between equal and 6 % faster on t550m, depending on where the
+    // buffers happen to lie in memory; it was never slower.
+    if (MODE == MODE_RECORD) {
+#pragma unroll
+        for (int m = 0; m < M; ++m) store4(sv.a(m, i), th[m]);
+        store4(sv.d(i), dbar);
+#pragma unroll
+        for (int m = 0; m < M; ++m) store4(sv.p(m, i), sent(d[m], sc));
+        return;
+    }
 #pragma unroll
     for (int m = 0; m < M; ++m) {
-        if (MODE == MODE_RECORD) {
-            store4(sv.a(m, i), th[m]);
-        } else {
-            f4 G = Dold;
-            if (MODE == MODE_EAGER) G = eager_gradient(d[m], p[m], Dold, sc);
-            f4 an = a[m], un = u[m];
-            outer_opt(an, un, G, sc);
-            store4(theta + m * stride + i, an);
-            store4(sv.a(m, i), an);
-            store4(sv.u(m, i), un);
-        }
+        f4 G = Dold;
+        if (MODE == MODE_EAGER) G = eager_gradient(d[m], p[m], Dold, sc);
+        outer_opt(a[m], u[m], G, sc);
+    }
+#pragma unroll
+    for (int m = 0; m < M; ++m) store4(theta + m * stride + i, a[m]);
+#pragma unroll
+    for (int m = 0; m < M; ++m) store4(sv.a(m, i), a[m]);
+    store4(sv.d(i), dbar);
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        store4(sv.u(m, i), u[m]);
         store4(sv.p(m, i), sent(d[m], sc));
     }
-    store4(sv.d(i), dbar);
 }
 
 // ------------------------------------------------------------------ LDS-staged path
@@ -468,6 +480,9 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
         DILOCO_REG_CASE(2)
         DILOCO_REG_CASE(3)
         DILOCO_REG_CASE(4)
+        DILOCO_REG_CASE(5)
+        DILOCO_REG_CASE(6)
+        DILOCO_REG_CASE(7)
         DILOCO_REG_CASE(8)
         default: break;
     }
