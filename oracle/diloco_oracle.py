@@ -33,7 +33,9 @@ trajectories, the paper's equivalent form of the eager combination (Section
 M = 1 and identical-worker reductions, the mu = 0, eta = 1 worker average, and
 published splitmix64 test vectors plus distribution tests for the noise.
 Parity unpinned: run_quadratic(overlap=2) against the paper, which gives no formula for the
-2-outer-steps overlap (the function is pinned to the reading stated in its docstring).
+2-outer-steps overlap (the function is pinned to the reading stated in its docstring);
+round_to_exmy against the paper's float8 / float4 runs, whose formats it does not state (the
+rounding is pinned to numpy's float16, torch's bfloat16 and enumerated float4 value sets).
 """
 from __future__ import annotations
 
@@ -101,7 +103,11 @@ def outer_standard(theta, a, u, eta, mu, nesterov=True):
 
 # --------------------------------------------------------------------------
 # Quantised communication (Section 3.2): the outer gradient a replica sends is rounded to
-# bfloat16.  Rounding is a decision about an integer code, so it is taken in the precision the
+# bfloat16, or to a small float of E exponent and Mn mantissa bits (the section names float8
+# and float4 in "ExMy" formats from a cited work without fixing E, Mn, the bias or the treatment
+# of overflow: reading below; parity with the paper's own runs is unpinned, the rounding itself
+# is pinned to IEEE half precision, to bfloat16 and to hand-enumerated float4 grids).
+# Rounding is a decision about an integer code, so it is taken in the precision the
 # wire format is produced from: the float32 difference of the stored float32 parameters.
 # --------------------------------------------------------------------------
 def round_to_bf16(x):
@@ -111,13 +117,45 @@ def round_to_bf16(x):
     return bits.astype(np.uint32).view(np.float32).astype(F64)
 
 
+def exmy_values(E, Mn, bias):
+    """All non-negative values of the sign / E exponent bits / Mn mantissa bits format with the
+    given exponent bias, indexed by their code c = (e << Mn) | f:
+        e = 0:  2^(1-bias) * f / 2^Mn            (zero and the subnormals)
+        e >= 1: 2^(e-bias) * (1 + f / 2^Mn)
+    Every code is a number: the format has no infinities and no NaNs."""
+    assert E >= 1 and Mn >= 0
+    c = np.arange(1 << (E + Mn), dtype=np.int64)
+    e, f = c >> Mn, c & ((1 << Mn) - 1)
+    frac = f.astype(F64) / float(1 << Mn)
+    return np.where(e == 0, np.ldexp(frac, 1 - bias), np.ldexp(1.0 + frac, e - bias))
+
+
+def round_to_exmy(x, E, Mn, bias):
+    """Nearest value of the format to each x (finite float32 values), ties to the even code,
+    magnitudes beyond the largest value saturate to it; the sign is kept."""
+    grid = exmy_values(E, Mn, bias)                   # ascending in the code
+    x = np.asarray(x, dtype=np.float32).astype(F64)
+    mag = np.abs(x)
+    hi = np.clip(np.searchsorted(grid, mag, side="left"), 1, len(grid) - 1)
+    lo = hi - 1
+    d_lo, d_hi = mag - grid[lo], grid[hi] - mag       # exact: neighbours of a float32 value
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))
+    out = np.where(take_hi, grid[hi], grid[lo])
+    out = np.where(mag >= grid[-1], grid[-1], out)
+    return np.copysign(out, x)
+
+
 def sent_outer_gradients(delta, a, theta, comm):
-    """What enters the all-reduce: Delta_m, or bf16(Delta_m) with Delta_m formed in float32."""
+    """What enters the all-reduce: Delta_m, or Delta_m formed in float32 and rounded to the wire
+    format: "bf16", or ("exmy", E, Mn, bias)."""
     if comm == "f32":
         return delta
-    assert comm == "bf16"
     d32 = (np.asarray(a, np.float32) - np.asarray(theta, np.float32)).astype(np.float32)
-    return round_to_bf16(d32)
+    if comm == "bf16":
+        return round_to_bf16(d32)
+    kind, E, Mn, bias = comm
+    assert kind == "exmy"
+    return round_to_exmy(d32, E, Mn, bias)
 
 
 # --------------------------------------------------------------------------

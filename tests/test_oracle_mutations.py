@@ -42,6 +42,14 @@ PINS = [
     lambda: P.test_noise_free_quadratic_converges("eager"),
     P.test_quadratic_run_single_replica_standard_matches_torch_optimizers,
     P.test_bf16_rounding_matches_the_library_conversion,
+    P.test_exmy_value_sets_of_the_four_bit_formats,
+    P.test_exmy_rounding_worked_cases,
+    P.test_exmy_rounding_is_ieee_half_precision_where_the_two_formats_coincide,
+    P.test_exmy_rounding_is_bfloat16_where_the_two_formats_coincide,
+    lambda: P.test_exmy_rounding_is_the_nearest_code_by_brute_force((2, 1, 11)),
+    lambda: P.test_exmy_rounding_is_the_nearest_code_by_brute_force((4, 3, 16)),
+    lambda: P.test_exmy_communication_stores_what_was_sent(O.outer_eager),
+    lambda: P.test_exmy_communication_stores_what_was_sent(O.outer_delayed),
     lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_eager),
     lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_delayed),
     S.test_checker_streaming_driver_reduces_to_the_plain_run,
@@ -206,6 +214,47 @@ def bf16_truncates(x):
     return bits.view(np.float32).astype(np.float64)
 
 
+def exmy_without_subnormals(E, Mn, bias):
+    g = ORIG["exmy_values"](E, Mn, bias).copy()
+    g[1:1 << Mn] = g[1 << Mn] if Mn else g[1:1]       # exponent code 0 flushes to the smallest normal
+    return np.sort(g)
+
+
+def exmy_ieee_top_exponent(E, Mn, bias):
+    """Top exponent code reserved, as IEEE formats do: the largest values go missing."""
+    g = ORIG["exmy_values"](E, Mn, bias)
+    return g[:len(g) - (1 << Mn)]
+
+
+def exmy_truncates(x, E, Mn, bias):
+    grid = O.exmy_values(E, Mn, bias)
+    x = np.asarray(x, dtype=np.float32).astype(np.float64)
+    lo = np.clip(np.searchsorted(grid, np.abs(x), side="right") - 1, 0, len(grid) - 1)
+    return np.copysign(grid[lo], x)
+
+
+def exmy_ties_away(x, E, Mn, bias):
+    grid = O.exmy_values(E, Mn, bias)
+    x = np.asarray(x, dtype=np.float32).astype(np.float64)
+    mag = np.abs(x)
+    hi = np.clip(np.searchsorted(grid, mag, side="left"), 1, len(grid) - 1)
+    out = np.where(grid[hi] - mag <= mag - grid[hi - 1], grid[hi], grid[hi - 1])
+    return np.copysign(np.where(mag >= grid[-1], grid[-1], out), x)
+
+
+def exmy_drops_sign(x, E, Mn, bias):
+    return np.abs(ORIG["round_to_exmy"](x, E, Mn, bias))
+
+
+def exmy_overflow_wraps_to_zero(x, E, Mn, bias):
+    out = ORIG["round_to_exmy"](x, E, Mn, bias)
+    return np.where(np.abs(np.asarray(x, np.float64)) > O.exmy_values(E, Mn, bias)[-1], 0.0, out)
+
+
+def sent_ignores_format(delta, a, theta, comm):
+    return ORIG["sent_outer_gradients"](delta, a, theta, "bf16" if comm != "f32" else "f32")
+
+
 def boundary_ignores_offset(t, H, offset=0):
     return t >= 1 and t % H == 0
 
@@ -233,6 +282,10 @@ MUTATIONS = [
     ("mix64", mix64_wrong_shift), ("standard_normal", normal_without_factor_two),
     ("standard_normal", normal_ignores_replica), ("round_to_bf16", bf16_truncates),
     ("is_boundary", boundary_ignores_offset),
+    ("exmy_values", exmy_without_subnormals), ("exmy_values", exmy_ieee_top_exponent),
+    ("round_to_exmy", exmy_truncates), ("round_to_exmy", exmy_ties_away),
+    ("round_to_exmy", exmy_drops_sign), ("round_to_exmy", exmy_overflow_wraps_to_zero),
+    ("sent_outer_gradients", sent_ignores_format),
     ("quadratic_gradient", quadratic_gradient_without_curvature),
 ]
 

@@ -467,6 +467,91 @@ def test_bf16_rounding_matches_the_library_conversion():
     assert O.round_to_bf16(np.float32(1.01171875)) == 1.015625
 
 
+def _wide_range_values(count, lo_exp, hi_exp, seed=5):
+    r = np.random.default_rng(seed)
+    return (r.standard_normal(count) * np.exp2(r.uniform(lo_exp, hi_exp, count))).astype(np.float32)
+
+
+def test_exmy_value_sets_of_the_four_bit_formats():
+    """The sixteen codes of the two 4-bit splits, enumerated by hand from the format definition:
+    E2M1 with bias 1 is the published float4 value set; E3M0 has powers of two only, and its
+    exponent code 0 holds nothing but zero (no mantissa bit, so no subnormal)."""
+    np.testing.assert_array_equal(O.exmy_values(2, 1, 1), [0, 0.5, 1, 1.5, 2, 3, 4, 6])
+    np.testing.assert_array_equal(O.exmy_values(3, 0, 3), [0, 0.25, 0.5, 1, 2, 4, 8, 16])
+    np.testing.assert_array_equal(O.exmy_values(2, 1, 3), np.array([0, 0.5, 1, 1.5, 2, 3, 4, 6]) / 4)
+    # float8 E4M3 with bias 7, every code a number: 2^-9 ... 2^8 * 1.875
+    g = O.exmy_values(4, 3, 7)
+    assert len(g) == 128 and g[1] == 2.0 ** -9 and g[8] == 2.0 ** -6 and g[-1] == 480.0
+    assert np.all(np.diff(g) > 0)
+
+
+def test_exmy_rounding_worked_cases():
+    """Ties go to the even code, overflow saturates, the sign survives, zero stays zero."""
+    x = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 7.0, 1e9, -0.3, -5.0, 0.0, 0.2500001, 0.7499999],
+                 np.float32)
+    want = np.array([0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0, 6.0, 6.0, -0.5, -4.0, 0.0, 0.5, 0.5])
+    np.testing.assert_array_equal(O.round_to_exmy(x, 2, 1, 1), want)
+    # E3M0: the midpoint of 2^k and 2^(k+1) goes to the even code (1.5 -> 2 = code 4, 3 -> 2, 6 -> 8)
+    x = np.array([1.5, 3.0, 6.0, 0.125, 0.1250001, 0.375, 100.0], np.float32)
+    np.testing.assert_array_equal(O.round_to_exmy(x, 3, 0, 3), [2.0, 2.0, 8.0, 0.0, 0.25, 0.5, 16.0])
+
+
+def test_exmy_rounding_is_ieee_half_precision_where_the_two_formats_coincide():
+    """E5M10 with bias 15 has the values of IEEE binary16 up to its largest finite one (65504),
+    subnormals included; there numpy's float16 conversion is an independent statement of
+    round-to-nearest-even."""
+    x = np.concatenate([_wide_range_values(400_000, -30, 16), np.float32([0, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25,
+                        65504, 2049, 2051, 1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11])])
+    x = x[np.abs(x) <= 65504]
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(O.round_to_exmy(x, 5, 10, 15), want)
+
+
+def test_exmy_rounding_is_bfloat16_where_the_two_formats_coincide():
+    """E8M7 with bias 127, against torch's float32 -> bfloat16 conversion (below 2^127, where
+    bfloat16 has numbers for every exponent code the format uses)."""
+    x = np.concatenate([_wide_range_values(200_000, -140, 126), rnd(1000, scale=1e-3).astype(np.float32)])
+    x = x[np.abs(x) < 2.0 ** 127]
+    want = torch.tensor(x).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_to_exmy(x, 8, 7, 127), want)
+    np.testing.assert_array_equal(O.round_to_exmy(x, 8, 7, 127), O.round_to_bf16(x))
+
+
+@pytest.mark.parametrize("fmt", [(2, 1, 11), (3, 0, 12), (4, 3, 16), (5, 2, 24), (3, 4, 12)])
+def test_exmy_rounding_is_the_nearest_code_by_brute_force(fmt):
+    """Against an exhaustive search over all signed codes, decoded bit field by bit field."""
+    E, Mn, bias = fmt
+    vals = []
+    for code in range(1 << (E + Mn)):
+        e, f = code >> Mn, code & ((1 << Mn) - 1)
+        vals.append((2.0 ** (1 - bias)) * f / 2 ** Mn if e == 0 else (2.0 ** (e - bias)) * (1 + f / 2 ** Mn))
+    x = np.concatenate([rnd(300, scale=1e-3), rnd(100, scale=1e-2), rnd(50, scale=1e-5), [0.0]]).astype(np.float32)
+    mids = [(vals[c] + vals[c + 1]) / 2 for c in range(len(vals) - 1)]
+    x = np.concatenate([x, np.float32(mids), -np.float32(mids[:5])])
+    got = O.round_to_exmy(x, E, Mn, bias)
+    for xi, gi in zip(x.astype(np.float64), got):
+        best = min(range(len(vals)), key=lambda c: (abs(abs(xi) - vals[c]), c % 2))
+        assert gi == np.copysign(vals[best], xi), (xi, gi, vals[best])
+    assert np.array_equal(O.round_to_exmy(got.astype(np.float32), E, Mn, bias), got)   # idempotent
+    order = np.argsort(x, kind="stable")
+    assert np.all(np.diff(got[order]) >= 0)                                         # monotone
+
+
+@pytest.mark.parametrize("fn", [O.outer_eager, O.outer_delayed])
+def test_exmy_communication_stores_what_was_sent(fn):
+    M, n = 3, 40
+    a0 = rnd(n, scale=0.02).astype(np.float32).astype(np.float64)
+    theta = (np.tile(a0, (M, 1)) - rnd(M, n, scale=1e-3)).astype(np.float32).astype(np.float64)
+    a, u, P, D = np.tile(a0, (M, 1)), np.zeros((M, n)), np.zeros((M, n)), np.zeros(n)
+    fn(theta.copy(), a, u, P, D, 0.7, 0.9, True, apply_update=False, comm=("exmy", 5, 10, 25))
+    d32 = (a0[None].astype(np.float32) - theta.astype(np.float32))
+    sent = (d32 * np.float32(1024.0)).astype(np.float16).astype(np.float64) / 1024.0   # bias 25 = half scaled by 2^-10
+    np.testing.assert_array_equal(P, sent)
+    np.testing.assert_allclose(D, sent.mean(axis=0), rtol=1e-14, atol=0)
+    assert np.max(np.abs(P - d32)) > 0
+
+
 @pytest.mark.parametrize("fn", [O.outer_eager, O.outer_delayed])
 def test_quantised_communication_keeps_the_stale_share_identity(fn):
     """With bf16 on the wire the stored previous local gradient is what was sent, so the eager
