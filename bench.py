@@ -233,6 +233,12 @@ def main():
         qms = timed(run_q, 5)[2]
         extra["outer_step_bf16_comm"] = {"ms": qms, "GBps": outer_bytes_fn(wl, n) / (qms * 1e-3) / 1e9}
 
+        def run_q4():   # float4 (E2M1, range placed at the outer gradients' scale) on the wire
+            d.outer_eager_packed(theta, state, n=n, variant=d.EAGER | d.COMM_EXMY(2, 1, 11), **okw)
+        run_q4()
+        q4ms = timed(run_q4, 5)[2]
+        extra["outer_step_fp4_comm"] = {"ms": q4ms, "GBps": outer_bytes_fn(wl, n) / (q4ms * 1e-3) / 1e9}
+
     # practical ceiling: plain copy with the same access shape
     set_shape(shape_default)
     cbuf = torch.empty(2 * n, dtype=torch.float32, device=dev)

@@ -57,10 +57,25 @@ typedef enum {
  * before it enters the mean, as if it had crossed the wire in bf16:
  *   prev_mean <- (1/M) sum_m bf16(Delta_m),  prev_local_m <- bf16(Delta_m)  (what was sent, so
  *   that next phase's eager combination removes exactly the replica's own stale share),
- * while the replica's own fresh Delta_m enters its eager combination unrounded.  The paper's
- * fp8 / fp4 formats and their scaling are defined in a work it cites and are not built.
+ * while the replica's own fresh Delta_m enters its eager combination unrounded.
  */
 #define DILOCO_COMM_BF16 0x100
+
+/*
+ * The same section names float8 and float4 wire formats of the "ExMy" kind without fixing them.
+ * DILOCO_COMM_EXMY(E, MN, BIAS), OR-ed into `variant` instead of DILOCO_COMM_BF16, rounds the
+ * outer gradients to the format with one sign bit, E exponent bits, MN mantissa bits and exponent
+ * bias BIAS, read this way: the values are +-2^(e-BIAS) (1 + f/2^MN) for exponent codes
+ * e = 1 .. 2^E - 1 and +-2^(1-BIAS) f/2^MN for e = 0 (zero and subnormals), f = 0 .. 2^MN - 1;
+ * every code is a number (no infinities, no NaNs); rounding is to the nearest value, ties to the
+ * even code; magnitudes beyond the largest value saturate to it.  BIAS places the format's range
+ * (a power-of-two scale chosen by the caller, e.g. E2M1 with BIAS 11 spans 2^-11 .. 1.5 * 2^-8).
+ * Limits: 1 <= E <= 8, 0 <= MN <= 10, E + MN <= 15, -128 <= BIAS <= 127, and the format must lie
+ * inside float32's normal range: 2^E - 1 - BIAS <= 127 and 1 - BIAS - MN >= -126; anything else is
+ * DILOCO_ERR_DTYPE.  The state buffers keep the rounded values as float32.
+ */
+#define DILOCO_COMM_EXMY(E, MN, BIAS) \
+    (0x200 | (((E) & 0xf) << 12) | (((MN) & 0xf) << 16) | (((BIAS) & 0xff) << 20))
 
 typedef enum {
     DILOCO_OK = 0,

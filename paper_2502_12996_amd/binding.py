@@ -19,6 +19,14 @@ LIB_PATH = os.path.join(_HERE, "libdiloco.so")
 F32, BF16 = 0, 1
 EAGER, DELAYED = 0, 1
 COMM_BF16 = 0x100   # OR into `variant`: outer gradients cross the wire in bf16
+
+
+def COMM_EXMY(E: int, Mn: int, bias: int) -> int:
+    """OR into `variant`: outer gradients cross the wire in the small-float format with E exponent
+    bits, Mn mantissa bits and the given exponent bias (DILOCO_COMM_EXMY of the header)."""
+    if not (0 <= E <= 15 and 0 <= Mn <= 15 and -128 <= bias <= 127):
+        raise ValueError("format fields out of range")
+    return 0x200 | (E << 12) | (Mn << 16) | ((bias & 0xFF) << 20)
 STATE_TILE = 8192    # DILOCO_STATE_TILE: elements per stream and tile of the packed outer state
 
 OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_HYPER, ERR_ALIAS, ERR_LAUNCH = range(8)

@@ -26,15 +26,46 @@ struct OuterScalars {
     float c_u;       // coefficient of the new velocity: lr*mu (Nesterov) or lr
     float inv_M;     // 1/M in fp32 (eager combination)
     double inv_M_d;  // 1/M in fp64 (mean)
-    int comm_bf16;   // outer gradients cross the wire in bf16 (Section 3.2)
+    int comm;        // wire format of the outer gradients (Section 3.2): COMM_F32 / COMM_BF16 / COMM_EXMY
+    int q_mant;      // ExMy: mantissa bits
+    int q_emin;      // ExMy: exponent of the spacing of the subnormals, 1 - bias - mantissa bits
+    int q_bias;      // ExMy: exponent bias
+    float q_max;     // ExMy: largest value of the format
 };
+enum { COMM_F32 = 0, COMM_BF16 = 1, COMM_EXMY = 2 };
 
-// What a replica sends into the all-reduce: Delta_m itself, or Delta_m rounded to bf16.
+// Nearest value of the small-float format, ties to the even code, saturating.  Around |d| the
+// format's values are the multiples of q = 2^max(floor(log2|d|) - mantissa bits, q_emin); |d|/q is
+// exact (a power-of-two scaling) and at most 2^(mantissa bits + 1), so rint() of it takes the
+// rounding decision exactly as the definition does.  Rounding up into the next binade lands on a
+// value of the format, or beyond q_max, where it saturates.  Without mantissa bits the parity of
+// |d|/q says nothing about the code, so the one possible tie (1.5 q) looks at the exponent code.
+__device__ __forceinline__ float round_exmy(float d, const OuterScalars& sc) {
+    const float ax = __builtin_fabsf(d);
+    const int k = (int)(__float_as_uint(ax) >> 23) - 127;
+    int qe = k - sc.q_mant;
+    qe = qe < sc.q_emin ? sc.q_emin : (qe > 126 ? 126 : qe);
+    const float q = __uint_as_float((uint32_t)(qe + 127) << 23);
+    const float iq = __uint_as_float((uint32_t)(127 - qe) << 23);
+    const float t = ax * iq;
+    float c = __builtin_rintf(t);
+    if (sc.q_mant == 0 && t == 1.5f) c = ((qe + sc.q_bias) & 1) ? 2.f : 1.f;
+    float r = c * q;
+    r = r > sc.q_max ? sc.q_max : r;
+    return __builtin_copysignf(r, d);
+}
+
+// What a replica sends into the all-reduce: Delta_m itself, or Delta_m rounded to the wire format.
 __device__ __forceinline__ float sent(float d, const OuterScalars& sc) {
-    return sc.comm_bf16 ? static_cast<float>(static_cast<__bf16>(d)) : d;
+    if (sc.comm == COMM_F32) return d;
+    if (sc.comm == COMM_BF16) return static_cast<float>(static_cast<__bf16>(d));
+    return round_exmy(d, sc);
 }
 __device__ __forceinline__ f4 sent(f4 d, const OuterScalars& sc) {
-    return sc.comm_bf16 ? __builtin_convertvector(__builtin_convertvector(d, bf4), f4) : d;
+    if (sc.comm == COMM_F32) return d;
+    if (sc.comm == COMM_BF16) return __builtin_convertvector(__builtin_convertvector(d, bf4), f4);
+    f4 r = {round_exmy(d.x, sc), round_exmy(d.y, sc), round_exmy(d.z, sc), round_exmy(d.w, sc)};
+    return r;
 }
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
@@ -444,9 +475,34 @@ __global__ __launch_bounds__(kMaxBlock) void repack_kernel(float* tiled, float* 
 }
 
 // ------------------------------------------------------------------ host dispatch
-static OuterScalars make_scalars(int M, double lr, double mu, int nesterov, int comm_bf16 = 0) {
+// Wire format out of the bits OR-ed into `variant` (DILOCO_COMM_BF16 / DILOCO_COMM_EXMY); false if
+// they name no format this library computes.
+static bool parse_comm(int variant, OuterScalars& sc) {
+    sc.comm = COMM_F32;
+    sc.q_mant = sc.q_emin = sc.q_bias = 0;
+    sc.q_max = 0.f;
+    const bool bf16 = variant & DILOCO_COMM_BF16, exmy = variant & 0x200;
+    if (bf16 && exmy) return false;
+    if (bf16) sc.comm = COMM_BF16;
+    if (!exmy) return (variant & ~0x1ff) == 0;
+    const int E = (variant >> 12) & 0xf, Mn = (variant >> 16) & 0xf;
+    const int bias = (int)(int8_t)((variant >> 20) & 0xff);
+    if ((variant & ~0x0ffff3ff) != 0 || E < 1 || E > 8 || Mn > 10 || E + Mn > 15) return false;
+    const int emax = (1 << E) - 1 - bias, emin_q = 1 - bias - Mn;
+    if (emax > 127 || emin_q < -126) return false;
+    sc.comm = COMM_EXMY;
+    sc.q_mant = Mn;
+    sc.q_emin = emin_q;
+    sc.q_bias = bias;
+    sc.q_max = (float)std::ldexp(2.0 - std::ldexp(1.0, -Mn), emax);
+    return true;
+}
+
+static OuterScalars make_scalars(int M, double lr, double mu, int nesterov) {
     OuterScalars sc;
-    sc.comm_bf16 = comm_bf16;
+    sc.comm = COMM_F32;
+    sc.q_mant = sc.q_emin = sc.q_bias = 0;
+    sc.q_max = 0.f;
     sc.mu = (float)mu;
     sc.c_g = nesterov ? (float)lr : 0.f;
     sc.c_u = nesterov ? (float)(lr * mu) : (float)lr;
@@ -535,8 +591,9 @@ extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, 
                                   int apply_update, void* stream) {
     if (!theta || !anchor || !vel || !prev_local || !prev_mean) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
-    const int comm_bf16 = (variant & DILOCO_COMM_BF16) ? 1 : 0;
-    variant = static_cast<diloco_variant>(variant & ~DILOCO_COMM_BF16);
+    OuterScalars comm;
+    if (!parse_comm(variant, comm)) return DILOCO_ERR_DTYPE;
+    variant = static_cast<diloco_variant>(variant & 0xff);
     if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
     if (int e = check_shape(M, n, stride)) return e;
     if (int e = check_shape(M, n, state_stride)) return e;
@@ -555,7 +612,8 @@ extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, 
     const bool vec_ok = aligned_to(theta, 4 * es) && aligned_to(anchor, 16) && aligned_to(vel, 16) &&
                         aligned_to(prev_local, 16) && aligned_to(prev_mean, 16) &&
                         (M == 1 || (stride % 4 == 0 && state_stride % 4 == 0));
-    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov, comm_bf16);
+    OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    sc.comm = comm.comm, sc.q_mant = comm.q_mant, sc.q_emin = comm.q_emin, sc.q_bias = comm.q_bias, sc.q_max = comm.q_max;
     const RowState sv{anchor, vel, prev_local, prev_mean, state_stride};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)
@@ -574,8 +632,9 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
                                          int apply_update, void* stream) {
     if (!theta || !state) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
-    const int comm_bf16 = (variant & DILOCO_COMM_BF16) ? 1 : 0;
-    variant = static_cast<diloco_variant>(variant & ~DILOCO_COMM_BF16);
+    OuterScalars comm;
+    if (!parse_comm(variant, comm)) return DILOCO_ERR_DTYPE;
+    variant = static_cast<diloco_variant>(variant & 0xff);
     if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
     if (int e = check_shape(M, n, stride)) return e;
     if (n > ((int64_t)1 << 40)) return DILOCO_ERR_SHAPE;
@@ -586,7 +645,8 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
     if (int e = check_alias(r, 2)) return e;
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
-    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov, comm_bf16);
+    OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    sc.comm = comm.comm, sc.q_mant = comm.q_mant, sc.q_emin = comm.q_emin, sc.q_bias = comm.q_bias, sc.q_max = comm.q_max;
     const TiledState sv{state, (int64_t)M};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)

@@ -32,7 +32,7 @@ class QuadraticSimulation:
 
     def __init__(self, M: int, n: int, H: int, variant: str = "eager", *, layout: str = "packed",
                  fragments: Optional[Sequence[Tuple[int, int]]] = None, overlap: int = 1,
-                 comm_bf16: bool = False, seed: int = W.BASE_SEED, noise_std: float = 0.1,
+                 comm_bf16: bool = False, comm_flags: int = 0, seed: int = W.BASE_SEED, noise_std: float = 0.1,
                  lr: float = 4e-4, beta1: float = 0.9, beta2: float = 0.95, eps: float = 1e-8,
                  weight_decay: float = 0.0, outer_lr: float = 0.7, outer_momentum: float = 0.9,
                  nesterov: bool = True, device: str = "cuda:0"):
@@ -46,7 +46,8 @@ class QuadraticSimulation:
         self.overlap, self.seed, self.noise_std = overlap, seed, noise_std
         self.adam = dict(lr=lr, beta1=beta1, beta2=beta2, eps=eps, weight_decay=weight_decay)
         self.outer = dict(outer_lr=outer_lr, outer_momentum=outer_momentum, nesterov=nesterov)
-        self.flags = (B.DELAYED if variant == "delayed" else B.EAGER) | (B.COMM_BF16 if comm_bf16 else 0)
+        self.flags = ((B.DELAYED if variant == "delayed" else B.EAGER) | (B.COMM_BF16 if comm_bf16 else 0)
+                      | comm_flags)      # comm_flags: e.g. binding.COMM_EXMY(2, 1, 11)
         self.t = 0
         f32 = dict(dtype=torch.float32, device=device)
         ns = (n + 3) & ~3                         # replica rows 16-byte aligned

@@ -426,12 +426,113 @@ def test_eager_with_bf16_communication(M, variant, apply, packed):
         assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"bf16 comm {variant} {k}")
 
 
-def test_unknown_variant_bits_are_rejected():
+# ------------------------------------------------------------------ small floats on the wire (Section 3.2)
+EXMY_FORMATS = [(2, 1, 11), (3, 0, 12), (4, 3, 16), (5, 2, 24), (5, 10, 15), (1, 0, 9), (7, 8, 60), (3, 4, -100),
+                (2, 10, 117), (4, 3, -112), (6, 0, 30)]
+
+
+def _rounding_probe(E, Mn, bias):
+    """float32 values that exercise the format: every exact tie between neighbouring values (all
+    of them for the small formats, 4096 sampled ones otherwise), the values themselves, the
+    largest value and beyond, the subnormal range and below it, both signs, zero."""
+    grid = O.exmy_values(E, Mn, bias)
+    r = np.random.default_rng(E * 1000 + Mn * 10 + bias % 7)
+    idx = np.arange(len(grid) - 1) if len(grid) <= 4096 else np.sort(r.choice(len(grid) - 1, 4096, replace=False))
+    ties = (grid[idx] + grid[idx + 1]) / 2
+    lo, hi = np.log2(grid[1]) - 4, np.log2(grid[-1]) + 2
+    wide = r.standard_normal(60_000) * np.exp2(r.uniform(lo, hi, 60_000))
+    x = np.concatenate([ties, -ties[::3], np.nextafter(ties.astype(np.float32), np.float32(0)),
+                        np.nextafter(ties.astype(np.float32), np.float32(np.inf)), grid[idx], wide,
+                        [0.0, grid[-1], -grid[-1], grid[-1] * 1.01, grid[-1] * 4, grid[1] / 2, grid[1] / 4]])
+    with np.errstate(over="ignore"):
+        x = x.astype(np.float32)
+    return x[np.isfinite(x)]
+
+
+@pytest.mark.parametrize("fmt", EXMY_FORMATS, ids=lambda f: "E%dM%db%d" % f)
+@pytest.mark.parametrize("packed", [False, True])
+def test_exmy_rounding_is_bit_exact(fmt, packed):
+    """theta = 0 and a = x make Delta = x exactly; the recorded previous local gradient is then the
+    library's rounding of x, compared bit for bit with the checker's."""
+    E, Mn, bias = fmt
+    x = _rounding_probe(E, Mn, bias)
+    n, M = ((len(x) + 1) // 2) | 1, 2                 # odd n: the scalar tail takes part
+    xs = torch.tensor(np.concatenate([x, np.zeros(2 * n - len(x), np.float32)]).reshape(2, n))
+    stride = (n + 3) & ~3
+    a = torch.zeros((M, stride), device=DEV)
+    a[:, :n] = xs.to(DEV)
+    theta, vel, P, D = torch.zeros_like(a), torch.zeros_like(a), torch.ones_like(a), torch.ones(n, device=DEV)
+    var = d.EAGER | d.COMM_EXMY(E, Mn, bias)
+    if packed:
+        state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+        d.pack_state(state, M, n, anchor=a, vel=vel, prev_local=P, prev_mean=D)
+        d.outer_eager_packed(theta, state, n=n, outer_lr=ETA, outer_momentum=MU, variant=var, apply_update=False)
+        d.unpack_state(state, M, n, prev_local=P, prev_mean=D)
+    else:
+        d.outer_eager(theta, a, vel, P, D, n=n, outer_lr=ETA, outer_momentum=MU, variant=var, apply_update=False)
+    torch.cuda.synchronize()
+    want = O.round_to_exmy(xs.numpy(), E, Mn, bias)
+    got = W.to_f64(P[:, :n])
+    bad = np.nonzero(got != want)
+    assert bad[0].size == 0, (fmt, xs.numpy()[bad][:5], got[bad][:5], want[bad][:5])
+    assert np.array_equal(np.signbit(got), np.signbit(want))
+    assert_close(W.to_f64(D), want.mean(axis=0), TOL_F32, f"mean of {fmt}")
+
+
+@pytest.mark.parametrize("M", [1, 2, 8, 9, 33])
+@pytest.mark.parametrize("variant,apply", [("eager", True), ("delayed", True), ("eager", False)])
+@pytest.mark.parametrize("packed,misalign", [(False, 0), (True, 0), (False, 1)])
+@pytest.mark.parametrize("fmt", [(2, 1, 11), (4, 3, 16)], ids=["fp4", "fp8"])
+def test_eager_with_exmy_communication(M, variant, apply, packed, misalign, fmt):
+    n = 20_003
+    wl = wl_for(M, n)
+    cut = (lambda v: v[:, misalign:misalign + n] if v.dim() == 2 else v)
+    st = {k: cut(v) for k, v in W.outer_state(wl, n, seed=61, stride=n + 8).items()}
+    ref = {k: W.to_f64(v) for k, v in st.items()}
+    fn = O.outer_eager if variant == "eager" else O.outer_delayed
+    fn(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU, True,
+       apply, comm=("exmy",) + fmt)
+    g = {k: cut(v.to(DEV)) for k, v in W.outer_state(wl, n, seed=61, stride=n + 8).items()}
+    var = (d.EAGER if variant == "eager" else d.DELAYED) | d.COMM_EXMY(*fmt)
+    if packed:
+        state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+        d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                     prev_mean=g["prev_mean"])
+        d.outer_eager_packed(g["theta"], state, n=n, outer_lr=ETA, outer_momentum=MU, variant=var,
+                             apply_update=apply)
+        d.unpack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                       prev_mean=g["prev_mean"])
+    else:
+        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], n=n,
+                      outer_lr=ETA, outer_momentum=MU, variant=var, apply_update=apply)
+    torch.cuda.synchronize()
+    assert np.array_equal(W.to_f64(g["prev_local"]), ref["prev_local"])        # codes: bit-exact
+    assert len(np.unique(np.abs(ref["prev_local"]))) <= 1 << (fmt[0] + fmt[1])
+    for k in ref:
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"exmy {fmt} comm {variant} {k}")
+
+
+@pytest.mark.parametrize("bits", [0x200, 0x400, 0x800, 1 << 28, 0x100 | 0x200 | (4 << 12) | (3 << 16),
+                                  "E0M3b0", "E9M1b0", "E5M11b0", "E8M7b127", "E8M2b100", "E4M3b-120", "E4M3b125", "E2M10b118", "E4M3b-113"])
+def test_unknown_variant_bits_are_rejected(bits):
+    if isinstance(bits, str):
+        E, rest = bits[1:].split("M")
+        Mn, bias = rest.split("b")
+        bits = d.COMM_EXMY(int(E), int(Mn), int(bias))
     g = _rows(2, 64, 3)
-    with pytest.raises(d.DilocoError) as ei:
-        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"],
-                      outer_lr=ETA, outer_momentum=MU, variant=0x200)
-    assert ei.value.status == d.binding.ERR_DTYPE
+    before = {k: v.clone() for k, v in g.items()}
+    for call in ("rows", "packed"):
+        with pytest.raises(d.DilocoError) as ei:
+            if call == "rows":
+                d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"],
+                              outer_lr=ETA, outer_momentum=MU, variant=bits)
+            else:
+                d.outer_eager_packed(g["theta"], torch.zeros(d.packed_state_elems(2, 64), device=DEV),
+                                     outer_lr=ETA, outer_momentum=MU, variant=bits)
+        assert ei.value.status == d.binding.ERR_DTYPE
+    torch.cuda.synchronize()
+    for k in g:
+        assert torch.equal(g[k], before[k])
 
 
 # ------------------------------------------------------------------ launch shapes the benchmark may pick
