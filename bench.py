@@ -32,6 +32,10 @@ def algorithmic_bytes(wl, n):
     return outer, inner
 
 
+def shape_json(sh):
+    return {"block": sh[0], "xcd_remap": sh[1], "wg_per_cu": sh[2]}
+
+
 def outer_bytes_fn(wl, n):
     return algorithmic_bytes(wl, n)[0]
 
@@ -129,18 +133,30 @@ def main():
         torch.cuda.synchronize()
         return sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(iters))
 
+    def set_shape(sh):
+        d.tune("block", sh[0])
+        d.tune("xcd_remap", sh[1])
+        d.tune("wg_per_cu", sh[2])
+
+    # (workgroup size, XCD-contiguous workgroup order, cap on resident workgroups per CU); block 0
+    # and cap -1 leave the choice to the launch itself
+    shape_default = (0, 0, -1)
+    candidates = ([(0, x, -1) for x in (0, 1)]
+                  + [(64, x, c) for x in (0, 1) for c in (2, 3, 4, 6, 8, 12, 16)]
+                  + [(256, x, c) for x in (0, 1) for c in (0, 1, 2, 3)]
+                  + [(b, x, 0) for x in (0, 1) for b in (128, 512)])
+
     def autotune(fn):
-        """Fastest (block, xcd_remap) of the launch shapes the library offers, by median of 5."""
+        """Fastest of the launch shapes the library offers, by median of 5."""
         best = None
-        for block in (64, 128, 256, 512):
-            for xcd in (0, 1):
-                d.tune("block", block)
-                d.tune("xcd_remap", xcd)
-                fn()
-                t = timed(fn, 5)[2]
-                if best is None or t < best[0]:
-                    best = (t, block, xcd)
-        return best[1], best[2]
+        for sh in candidates:
+            set_shape(sh)
+            fn()
+            t = timed(fn, 5)[2]
+            if best is None or t < best[0]:
+                best = (t, sh)
+        set_shape(shape_default)
+        return best[1]
 
     def run_rows():
         d.outer_eager(theta, st["anchor"], st["vel"], st["prev_local"], st["prev_mean"], n=n, **okw)
@@ -149,13 +165,8 @@ def main():
         d.inner_adamw(theta, m1, m2, grad, n=n, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
                       weight_decay=wl.weight_decay, step=t)
 
-    shape_default = (d.tune_get("block"), d.tune_get("xcd_remap"))
     shape_rows = autotune(run_rows) if args.autotune else shape_default
     shape_inner = autotune(run_inner) if args.autotune else shape_default
-
-    def set_shape(sh):
-        d.tune("block", sh[0])
-        d.tune("xcd_remap", sh[1])
 
     # the eager step on caller-layout rows, timed on its own (secondary figure)
     set_shape(shape_rows)
@@ -239,19 +250,33 @@ def main():
         q4ms = timed(run_q4, 5)[2]
         extra["outer_step_fp4_comm"] = {"ms": q4ms, "GBps": outer_bytes_fn(wl, n) / (q4ms * 1e-3) / 1e9}
 
-    # practical ceiling: plain copy with the same access shape
-    set_shape(shape_default)
+    # the standard (Algorithm 1) outer step on the same replicas: shared outer parameters
+    es = 2 if bf16 else 4
+    sa = W.normal((n,), wl.std_anchor, tag="anchor", device=dev)
+    sv = torch.zeros(n, dtype=torch.float32, device=dev)
+
+    def run_sync():
+        d.outer_sync(theta, sa, sv, **okw)
+    shape_sync = autotune(run_sync) if args.autotune else shape_default
+    set_shape(shape_sync)
+    run_sync()
+    sms = timed(run_sync, 7)[3]
+    extra["outer_step_standard"] = {"ms": sms, "GBps": (2 * M * es + 16) * n / (sms * 1e-3) / 1e9,
+                                    "launch": shape_json(shape_sync)}
+    del sa, sv
+
+    # practical ceiling: a plain copy kernel with the same access shape, in its best launch shape
     cbuf = torch.empty(2 * n, dtype=torch.float32, device=dev)
     src, dst = cbuf[:n], cbuf[n:]
-    cp = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    for _ in range(3):
-        d.sim_stream_copy(dst, src)
-    cp[0].record()
-    for _ in range(10):
-        d.sim_stream_copy(dst, src)
-    cp[1].record()
-    torch.cuda.synchronize()
-    copy_gbps = 10 * 8 * n / (cp[0].elapsed_time(cp[1]) * 1e-3) / 1e9
+    copy_ms = None
+    for sh in [(b, x, 0) for b in (64, 256, 512) for x in (0, 1)]:
+        set_shape(sh)
+        for _ in range(3):
+            d.sim_stream_copy(dst, src)
+        t = timed(lambda: d.sim_stream_copy(dst, src), 10)[5]
+        copy_ms = t if copy_ms is None else min(copy_ms, t)
+    set_shape(shape_default)
+    copy_gbps = 8 * n / (copy_ms * 1e-3) / 1e9
 
     outer_bytes, inner_bytes = algorithmic_bytes(wl, n)
     outer_gbps = outer_bytes / (outer_ms * 1e-3) / 1e9
@@ -268,14 +293,13 @@ def main():
                                f"fused eager outer step per step",
                    "M": M, "N": n, "theta_dtype": wl.theta_dtype, "stride_pad": args.pad,
                    "outer_state_layout": args.layout,
-                   "launch": {"outer": {"block": shape_outer[0], "xcd_remap": shape_outer[1]},
-                              "inner": {"block": shape_inner[0], "xcd_remap": shape_inner[1]}}},
+                   "launch": {"outer": shape_json(shape_outer), "inner": shape_json(shape_inner)}},
         "outer_step": {"ms": outer_ms, "params_per_s": n / (outer_ms * 1e-3),
                        "worker_params_per_s": M * n / (outer_ms * 1e-3), "GBps": outer_gbps,
                        "frac_of_peak": outer_gbps / HBM_PEAK_GBPS},
         "outer_step_rows_layout": {"ms": rows_ms, "GBps": outer_bytes / (rows_ms * 1e-3) / 1e9,
                                    "frac_of_peak": outer_bytes / (rows_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                                   "launch": {"block": shape_rows[0], "xcd_remap": shape_rows[1]}},
+                                   "launch": shape_json(shape_rows)},
         "inner_step": {"ms": inner_ms, "worker_params_per_s": M * n / (inner_ms * 1e-3),
                        "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS},
         **extra,

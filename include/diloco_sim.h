@@ -61,10 +61,17 @@ int diloco_sim_quadratic_loss(const float* theta, int M, int64_t n, int64_t stri
 int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream);
 
 /*
- * Launch tuning for measurements.  Keys: "block" (threads per workgroup: 64..512,
- * power of two), "xcd_remap" (0/1: give each of the 8 XCDs a contiguous slice of the
- * index space), "generic_path" (eager kernel for replica counts without a register
- * instantiation: 0 = choose, 1 = LDS-staged, 2 = two-pass).
+ * Launch tuning for measurements.  Keys:
+ *   "block"        threads per workgroup of the streaming kernels: 64..512, power of two; 0 (the
+ *                  default) lets each launch choose: one-wavefront workgroups, throttled as below.
+ *   "xcd_remap"    0/1: give each of the 8 XCDs a contiguous slice of the index space.
+ *   "wg_per_cu"    at most this many workgroups of a streaming kernel resident on a compute unit
+ *                  (1..32; enforced with dynamic LDS the kernel never touches); 0: no cap; -1 (the
+ *                  default): with "block" 0 the launch picks the cap that puts about 32-64 KB of
+ *                  loads in flight per compute unit, with an explicit "block" there is no cap.
+ *   "generic_path" eager kernel for replica counts without a register instantiation: 0 = choose,
+ *                  1 = LDS-staged, 2 = two-pass.
+ * Results do not depend on any of them.
  * Returns DILOCO_OK or DILOCO_ERR_HYPER for an unknown key / value.  Not thread safe.
  */
 int diloco_tune(const char* key, int value);

@@ -161,15 +161,18 @@ static AdamScalars make_adam(double lr, double b1, double b2, double eps, double
 template <typename PT, typename GT>
 static int launch_adamw(void* theta, void* m1, void* m2, const void* grad, int M, int64_t n,
                         int64_t stride, const AdamScalars& sc, bool vec_ok, hipStream_t st) {
-    const int block = tuning().block;
+    // a wavefront of the vector kernel loads theta, m1, m2 and the gradient of 256 parameters
+    const Shape shape = launch_shape((int64_t)64 * 4 * (3 * sizeof(PT) + sizeof(GT)), 32 * 1024);
+    const int block = shape.block;
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(threads, block);
-    if (vec_ok)
-        hipLaunchKernelGGL((adamw_vec_kernel<PT, GT>), dim3(g.blocks, M), dim3(block), 0, st,
+    if (vec_ok) {
+        if (!grant_lds(&adamw_vec_kernel<PT, GT>, shape.lds)) return DILOCO_ERR_LAUNCH;
+        hipLaunchKernelGGL((adamw_vec_kernel<PT, GT>), dim3(g.blocks, M), dim3(block), shape.lds, st,
                            static_cast<PT*>(theta), static_cast<PT*>(m1), static_cast<PT*>(m2),
                            static_cast<const GT*>(grad), n, stride, sc, g.per_xcd);
-    else
+    } else
         hipLaunchKernelGGL((adamw_scalar_kernel<PT, GT>), dim3(g.blocks, M), dim3(block), 0, st,
                            static_cast<PT*>(theta), static_cast<PT*>(m1), static_cast<PT*>(m2),
                            static_cast<const GT*>(grad), n, stride, sc, g.per_xcd);
@@ -233,11 +236,14 @@ extern "C" int diloco_sim_quadratic_inner(float* theta, float* m1, float* m2, in
     if (n == 0) return DILOCO_OK;
     const AdamScalars sc = make_adam(lr, beta1, beta2, eps, weight_decay, step);
     const uint64_t k0 = mix64(seed + kGolden * (uint64_t)(step + 1));
-    const int block = tuning().block;
+    // a wavefront loads h, theta* and theta, m1, m2 of every replica, 16 B a lane each
+    const Shape shape = launch_shape((int64_t)64 * 16 * (2 + 3 * M), 64 * 1024);
+    const int block = shape.block;
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(threads, block);
-    hipLaunchKernelGGL(quadratic_inner_kernel, dim3(g.blocks), dim3(block), 0,
+    if (!grant_lds(&quadratic_inner_kernel, shape.lds)) return DILOCO_ERR_LAUNCH;
+    hipLaunchKernelGGL(quadratic_inner_kernel, dim3(g.blocks), dim3(block), shape.lds,
                        static_cast<hipStream_t>(stream), theta, m1, m2, h, theta_star, M, n, stride,
                        (float)noise_std, k0, index_base, sc, g.per_xcd);
     return launch_status();

@@ -76,11 +76,54 @@ __device__ __forceinline__ int64_t logical_block(int64_t per_xcd) {
 
 // ---------------------------------------------------------------- host side
 struct Tuning {
-    int block = 256;
+    int block = 0;         // threads per workgroup of the streaming kernels; 0: chosen per launch
     int xcd_remap = 0;
     int generic_path = 0;  // eager kernel for M without a register instantiation: 0 auto, 1 LDS, 2 two-pass
+    int wg_per_cu = -1;    // most workgroups of a streaming kernel resident on a CU; 0: no cap, -1: chosen per launch
 };
 Tuning& tuning();
+
+constexpr int kLdsPerCu = 160 * 1024;  // gfx950
+
+// Workgroup size and occupancy throttle of one launch.
+//
+// This chip's HBM pipeline is fastest with a few tens of KB of loads in flight per CU, and gets
+// slower, not faster, with full occupancy (measured: AdamW 6.2 -> 6.6 TB/s, standard outer step
+// 5.8 -> 6.4 TB/s at M = 8).  The throttle is dynamic LDS the kernel never touches, sized so that
+// only `cap` workgroups fit a CU's 160 KB.  Left to itself (block 0, wg_per_cu -1) a launch uses
+// one-wavefront workgroups and as many of them per CU as bring `target_bytes` of loads in flight,
+// given that a wavefront issues `wave_load_bytes` before its first store (at least 2; no throttle
+// from 32 up).  An explicit block size switches the throttle off unless wg_per_cu is set too.
+struct Shape {
+    int block;
+    size_t lds;
+};
+inline Shape launch_shape(int64_t wave_load_bytes, int64_t target_bytes) {
+    const Tuning& t = tuning();
+    Shape s{t.block ? t.block : 64, 0};
+    int cap = t.wg_per_cu;
+    if (cap < 0) {
+        cap = 0;
+        if (!t.block) {
+            cap = (int)((target_bytes + wave_load_bytes - 1) / wave_load_bytes);
+            cap = cap < 2 ? 2 : (cap >= 32 ? 0 : cap);
+        }
+    }
+    if (cap > 0) {
+        s.lds = (size_t)(kLdsPerCu / cap);
+        s.lds -= s.lds % 1280;
+    }
+    return s;
+}
+// Workgroup size of the kernels that take no throttle.
+inline int plain_block() { return tuning().block ? tuning().block : 256; }
+// More than 48 KB of dynamic LDS has to be granted per kernel; false if the runtime refuses.
+template <typename K>
+inline bool grant_lds(K kernel, size_t lds) {
+    if (lds <= 48 * 1024) return true;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)lds) == hipSuccess;
+}
 
 struct Range {
     const void* p;

@@ -70,7 +70,6 @@ __device__ __forceinline__ f4 sent(f4 d, const OuterScalars& sc) {
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
-constexpr int kLdsPerCu = 160 * 1024;  // gfx950
 constexpr int kMinStagedWaves = 6;     // LDS path only while this many wavefronts fit a CU
 constexpr int kTileShift = 13;  // DILOCO_STATE_TILE = 8192 elements
 constexpr int64_t kTile = (int64_t)1 << kTileShift;
@@ -514,7 +513,9 @@ static OuterScalars make_scalars(int M, double lr, double mu, int nesterov) {
 template <typename TT, int MODE, typename SV>
 static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, const OuterScalars& sc,
                         bool vec_ok, hipStream_t st) {
-    const int block = tuning().block;
+    // a wavefront of the vector kernels loads theta_m, a_m, u_m, P_m of every replica and D: 16 B a lane each
+    const Shape shape = launch_shape((int64_t)64 * ((3 * M + 1) * 16 + M * 4 * (int64_t)sizeof(TT)), 64 * 1024);
+    const int block = shape.block;
     if (!vec_ok) {
         if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
         Grid g = make_grid(n, block);
@@ -527,8 +528,9 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
 #define DILOCO_REG_CASE(MM)                                                                               \
     case MM: {                                                                                            \
         Grid g = make_grid(threads, block);                                                               \
-        hipLaunchKernelGGL((outer_eager_reg_kernel<MM, TT, MODE, SV>), dim3(g.blocks), dim3(block), 0, st, \
-                           theta, sv, n, stride, sc, g.per_xcd);                                          \
+        if (!grant_lds(&outer_eager_reg_kernel<MM, TT, MODE, SV>, shape.lds)) return DILOCO_ERR_LAUNCH;   \
+        hipLaunchKernelGGL((outer_eager_reg_kernel<MM, TT, MODE, SV>), dim3(g.blocks), dim3(block),       \
+                           shape.lds, st, theta, sv, n, stride, sc, g.per_xcd);                           \
         return launch_status();                                                                           \
     }
     switch (M) {
@@ -670,7 +672,7 @@ static int repack(bool to_tiled, float* state, int M, int64_t n, float* anchor, 
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(anchor, 16) && aligned_to(vel, 16) && aligned_to(prev_local, 16) &&
                         aligned_to(prev_mean, 16) && (M == 1 || state_stride % 4 == 0);
-    const int block = tuning().block;
+    const int block = plain_block();
     const int64_t threads = vec_ok ? (n + 3) >> 2 : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(threads, block);
@@ -707,13 +709,17 @@ extern "C" int diloco_unpack_state(const float* state, int M, int64_t n, float* 
 template <typename TT>
 static int launch_sync(TT* theta, float* anchor, float* vel, float* mean_out, int M, int64_t n,
                        int64_t stride, const OuterScalars& sc, bool vec_ok, hipStream_t st) {
-    const int block = tuning().block;
+    // a wavefront of the vector kernel loads theta_m of every replica, the anchor and the velocity
+    const Shape shape = launch_shape((int64_t)64 * (2 * 16 + M * 4 * (int64_t)sizeof(TT)), 64 * 1024);
+    const int block = shape.block;
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(threads, block);
-    if (vec_ok)
-        hipLaunchKernelGGL((outer_sync_vec_kernel<TT>), dim3(g.blocks), dim3(block), 0, st, theta,
+    if (vec_ok) {
+        if (!grant_lds(&outer_sync_vec_kernel<TT>, shape.lds)) return DILOCO_ERR_LAUNCH;
+        hipLaunchKernelGGL((outer_sync_vec_kernel<TT>), dim3(g.blocks), dim3(block), shape.lds, st, theta,
                            anchor, vel, mean_out, M, n, stride, sc, g.per_xcd);
+    }
     else
         hipLaunchKernelGGL((outer_sync_scalar_kernel<TT>), dim3(g.blocks), dim3(block), 0, st, theta,
                            anchor, vel, mean_out, M, n, stride, sc, g.per_xcd);
@@ -751,7 +757,7 @@ extern "C" int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, i
 
 template <typename TT, typename AV>
 static int launch_reset(void* theta, AV av, int M, int64_t n, int64_t stride, bool vec_ok, hipStream_t st) {
-    const int block = tuning().block;
+    const int block = plain_block();
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(threads, block);

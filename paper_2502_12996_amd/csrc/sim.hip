@@ -112,11 +112,13 @@ extern "C" int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, v
     Range r[2] = {{dst, n * 4, true}, {src, n * 4, false}};
     if (int e = check_alias(r, 2)) return e;
     if (n == 0) return DILOCO_OK;
-    const int block = tuning().block;
+    const Shape shape = launch_shape(64 * 16, 64 * 1024);  // one load a lane: never throttled by itself
+    const int block = shape.block;
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(threads, block);
-    hipLaunchKernelGGL(stream_copy_kernel, dim3(g.blocks), dim3(block), 0,
+    if (!grant_lds(&stream_copy_kernel, shape.lds)) return DILOCO_ERR_LAUNCH;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(g.blocks), dim3(block), shape.lds,
                        static_cast<hipStream_t>(stream), dst, src, n, g.per_xcd);
     return launch_status();
 }
@@ -144,7 +146,7 @@ extern "C" int64_t diloco_stream_boundary_count(int64_t t, int64_t H, int F, int
 extern "C" int diloco_tune(const char* key, int value) {
     if (!key) return DILOCO_ERR_NULL;
     if (!std::strcmp(key, "block")) {
-        if (value < 64 || value > kMaxBlock || (value & (value - 1))) return DILOCO_ERR_HYPER;
+        if (value != 0 && (value < 64 || value > kMaxBlock || (value & (value - 1)))) return DILOCO_ERR_HYPER;
         tuning().block = value;
         return DILOCO_OK;
     }
@@ -158,6 +160,11 @@ extern "C" int diloco_tune(const char* key, int value) {
         tuning().generic_path = value;
         return DILOCO_OK;
     }
+    if (!std::strcmp(key, "wg_per_cu")) {
+        if (value < -1 || value > 32) return DILOCO_ERR_HYPER;
+        tuning().wg_per_cu = value;
+        return DILOCO_OK;
+    }
     return DILOCO_ERR_HYPER;
 }
 
@@ -166,6 +173,7 @@ extern "C" int diloco_tune_get(const char* key) {
     if (!std::strcmp(key, "block")) return tuning().block;
     if (!std::strcmp(key, "xcd_remap")) return tuning().xcd_remap;
     if (!std::strcmp(key, "generic_path")) return tuning().generic_path;
+    if (!std::strcmp(key, "wg_per_cu")) return tuning().wg_per_cu;
     return -1;
 }
 

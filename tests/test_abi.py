@@ -177,6 +177,10 @@ def test_sim_validation_and_tuning(lib):
     assert lib.diloco_tune(b"block", 2048) == B.ERR_HYPER
     assert lib.diloco_tune(b"nope", 1) == B.ERR_HYPER
     assert lib.diloco_tune(b"block", old) == B.OK
+    assert old == 0 and lib.diloco_tune_get(b"wg_per_cu") == -1 and lib.diloco_tune_get(b"xcd_remap") == 0
+    assert lib.diloco_tune(b"wg_per_cu", 33) == B.ERR_HYPER and lib.diloco_tune(b"wg_per_cu", -2) == B.ERR_HYPER
+    assert lib.diloco_tune(b"wg_per_cu", 4) == B.OK and lib.diloco_tune_get(b"wg_per_cu") == 4
+    assert lib.diloco_tune(b"wg_per_cu", -1) == B.OK
     assert lib.diloco_tune_get(b"nope") == -1
 
 

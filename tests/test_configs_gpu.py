@@ -300,8 +300,8 @@ def test_quadratic_forty_phases(variant, lr_div):
           f"loss deviation {worst_loss:.2e}, worst state error after {H * wl.phases} steps {worst_state:.2e}")
 
 
-@pytest.mark.parametrize("block,xcd", [(256, 0), (64, 1), (512, 1)])
-def test_t550m_packed_state_eager_outer_step_per_call(block, xcd):
+@pytest.mark.parametrize("block,xcd,cap", [(0, 0, -1), (256, 0, 0), (64, 1, 3), (512, 1, 0)])
+def test_t550m_packed_state_eager_outer_step_per_call(block, xcd, cap):
     """Config 3 through the packed-state entry point, in launch shapes the benchmark picks from."""
     wl = W.WORKLOADS["t550m"]
     M, n = wl.M, wl.n
@@ -315,11 +315,13 @@ def test_t550m_packed_state_eager_outer_step_per_call(block, xcd):
         st[k].zero_()
     d.tune("block", block)
     d.tune("xcd_remap", xcd)
+    d.tune("wg_per_cu", cap)
     try:
         d.outer_eager_packed(st["theta"], state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
     finally:
-        d.tune("block", 256)
+        d.tune("block", 0)
         d.tune("xcd_remap", 0)
+        d.tune("wg_per_cu", -1)
     d.unpack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
                    prev_mean=st["prev_mean"])
     torch.cuda.synchronize()

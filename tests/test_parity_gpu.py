@@ -536,29 +536,37 @@ def test_unknown_variant_bits_are_rejected(bits):
 
 
 # ------------------------------------------------------------------ launch shapes the benchmark may pick
-@pytest.fixture
-def launch_shape(request):
-    block, xcd = request.param
+DEFAULT_SHAPE = (0, 0, -1)        # workgroup size and occupancy cap chosen per launch, natural workgroup order
+
+
+def set_shape(block, xcd, cap):
     d.tune("block", block)
     d.tune("xcd_remap", xcd)
-    yield block, xcd
-    d.tune("block", 256)
-    d.tune("xcd_remap", 0)
+    d.tune("wg_per_cu", cap)
 
 
-@pytest.mark.parametrize("launch_shape", [(64, 0), (64, 1), (128, 1), (256, 1), (512, 0), (512, 1)], indirect=True)
+@pytest.fixture
+def launch_shape(request):
+    set_shape(*request.param)
+    yield request.param
+    set_shape(*DEFAULT_SHAPE)
+
+
+@pytest.mark.parametrize("launch_shape", [(64, 0, 0), (64, 1, -1), (128, 1, 0), (256, 0, 0), (256, 1, 0), (512, 0, 0),
+                                          (512, 1, 0), (64, 0, 1), (64, 0, 3), (64, 1, 32), (128, 0, 5), (256, 0, 1),
+                                          (256, 1, 2), (512, 0, 1), (0, 1, 2), (0, 0, 0)], indirect=True)
 def test_every_launch_shape_gives_the_same_bits(launch_shape):
-    """Workgroup size and XCD-contiguous workgroup order only change who computes what."""
+    """Workgroup size, XCD-contiguous workgroup order and the cap on resident workgroups (dynamic
+    LDS up to a CU's whole 160 KB) only change who computes what, and when."""
     M, n = 8, 150_003                     # > 32 workgroups at every size, ragged tail
     # eager, rows and packed, against the default shape
     want = _rows(M, n, 73)
     got = _rows(M, n, 73)
     pk = _rows(M, n, 73)
-    block, xcd = launch_shape
-    d.tune("block", 256); d.tune("xcd_remap", 0)
+    set_shape(*DEFAULT_SHAPE)
     d.outer_eager(want["theta"], want["anchor"], want["vel"], want["prev_local"], want["prev_mean"],
                   outer_lr=ETA, outer_momentum=MU)
-    d.tune("block", block); d.tune("xcd_remap", xcd)
+    set_shape(*launch_shape)
     d.outer_eager(got["theta"], got["anchor"], got["vel"], got["prev_local"], got["prev_mean"],
                   outer_lr=ETA, outer_momentum=MU)
     state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
