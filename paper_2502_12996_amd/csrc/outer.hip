@@ -70,7 +70,7 @@ __device__ __forceinline__ f4 sent(f4 d, const OuterScalars& sc) {
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
-constexpr int kMinStagedWaves = 6;     // LDS path only while this many wavefronts fit a CU
+constexpr int kMinStagedWaves = 2;     // LDS path only while this many wavefronts fit a CU
 constexpr int kTileShift = 13;  // DILOCO_STATE_TILE = 8192 elements
 constexpr int64_t kTile = (int64_t)1 << kTileShift;
 static_assert(kTile == DILOCO_STATE_TILE, "header and kernels disagree on the state tile");
@@ -234,67 +234,99 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
     }
 }
 
-// ------------------------------------------------------------------ LDS-staged path
-// Any M: a_m and Delta_m are parked in LDS (32 bytes per thread and replica) between the two
-// loops.  A thread only reads back what it wrote itself, so no barrier is needed.
-template <typename TT, int MODE, typename SV>
-__global__ __launch_bounds__(kMaxBlock) void outer_eager_lds_kernel(TT* __restrict__ theta, SV sv, int M,
-                                                                    int64_t n, int64_t stride, OuterScalars sc,
-                                                                    int64_t per_xcd) {
-    extern __shared__ f4 stage[];  // [M][2][blockDim.x]
-    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
-    const int64_t nvec = n >> 2;
-    if (v >= nvec) {
-        if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, M, n, stride, sc);
-        return;
-    }
-    const int64_t i = v << 2;
-    const int B = blockDim.x, tid = threadIdx.x;
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-#pragma unroll 4
-    for (int m = 0; m < M; ++m) {
-        f4 a = load4(sv.a(m, i));
-        f4 th = load4(theta + m * stride + i);
-        f4 d = a - th;
-        const f4 q = sent(d, sc);
-        s0 += (double)q.x;
-        s1 += (double)q.y;
-        s2 += (double)q.z;
-        s3 += (double)q.w;
-        stage[(2 * m) * B + tid] = (MODE == MODE_RECORD) ? th : a;
-        stage[(2 * m + 1) * B + tid] = d;
-    }
-    f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
-               (float)(s3 * sc.inv_M_d)};
-    f4 Dold = {0.f, 0.f, 0.f, 0.f};
-    if (MODE != MODE_RECORD) Dold = load4(sv.d(i));
-    for (int m = 0; m < M; ++m) {
-        f4 an = stage[(2 * m) * B + tid];
-        f4 d = stage[(2 * m + 1) * B + tid];
-        if (MODE == MODE_RECORD) {
-            store4(sv.a(m, i), an);  // holds theta_m
-        } else {
-            f4 un = load4(sv.u(m, i));
-            f4 G = Dold;
-            if (MODE == MODE_EAGER) G = eager_gradient(d, load4(sv.p(m, i)), Dold, sc);
-            outer_opt(an, un, G, sc);
-            store4(theta + m * stride + i, an);
-            store4(sv.a(m, i), an);
-            store4(sv.u(m, i), un);
+// ------------------------------------------------------------------ any M: replicas in groups
+// For replica counts without a register instantiation the sweep walks the replicas in groups of
+// kGroup, every group's loads issued together (a wavefront that waits for one replica at a time
+// needs far more resident wavefronts than the staging leaves room for).  Sum and update keep the
+// order m = 0, 1, ... of the register kernel: same bits.
+constexpr int kGroup = 8;
+
+// First pass over one group: Delta_m = a_m - theta_m into the running sum; with LDS staging the
+// values the second pass needs are parked (a_m, or theta_m when only recording, and Delta_m).
+template <typename TT, int MODE, typename SV, bool FULL, bool STAGE>
+__device__ __forceinline__ void group_reduce(const TT* __restrict__ theta, const SV& sv, int m0, int cnt,
+                                             int64_t i, int64_t stride, const OuterScalars& sc, f4* stage,
+                                             int tid, double& s0, double& s1, double& s2, double& s3) {
+    f4 a[kGroup], th[kGroup];
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j)
+        if (FULL || j < cnt) {
+            a[j] = load4(sv.a(m0 + j, i));
+            th[j] = load4(theta + (m0 + j) * stride + i);
         }
-        store4(sv.p(m, i), sent(d, sc));
-    }
-    store4(sv.d(i), dbar);
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j)
+        if (FULL || j < cnt) {
+            const f4 d = a[j] - th[j];
+            const f4 q = sent(d, sc);
+            s0 += (double)q.x;
+            s1 += (double)q.y;
+            s2 += (double)q.z;
+            s3 += (double)q.w;
+            if (STAGE) {
+                stage[(2 * (m0 + j)) * 64 + tid] = (MODE == MODE_RECORD) ? th[j] : a[j];
+                stage[(2 * (m0 + j) + 1) * 64 + tid] = d;
+            }
+        }
 }
 
-// ------------------------------------------------------------------ two-pass vector path
-// Any M, no staging: the second loop re-reads theta_m and a_m (2 of the 8M+2 accesses per
-// index are read twice).  Keeps full occupancy when M is too large for the LDS path to leave
-// enough wavefronts per CU.
-template <typename TT, int MODE, typename SV>
-__global__ __launch_bounds__(kMaxBlock) void outer_eager_twopass_kernel(TT* __restrict__ theta, SV sv, int M,
-                                                                        int64_t n, int64_t stride,
-                                                                        OuterScalars sc, int64_t per_xcd) {
+// Second pass over one group.  STAGE: a_m (theta_m) and Delta_m come back from LDS; otherwise
+// theta_m and a_m are read again.
+template <typename TT, int MODE, typename SV, bool FULL, bool STAGE>
+__device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& sv, int m0, int cnt, int64_t i,
+                                             int64_t stride, const OuterScalars& sc, const f4* stage, int tid,
+                                             f4 Dold) {
+    f4 a[kGroup], d[kGroup], u[kGroup], p[kGroup];
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j)
+        if (FULL || j < cnt) {
+            if (!STAGE) {
+                a[j] = load4(sv.a(m0 + j, i));
+                d[j] = load4(theta + (m0 + j) * stride + i);  // theta for now
+            }
+            if (MODE != MODE_RECORD) u[j] = load4(sv.u(m0 + j, i));
+            if (MODE == MODE_EAGER) p[j] = load4(sv.p(m0 + j, i));
+        }
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j)
+        if (FULL || j < cnt) {
+            if (STAGE) {
+                a[j] = stage[(2 * (m0 + j)) * 64 + tid];  // theta_m when only recording
+                d[j] = stage[(2 * (m0 + j) + 1) * 64 + tid];
+            } else {
+                const f4 th = d[j];
+                d[j] = a[j] - th;
+                if (MODE == MODE_RECORD) a[j] = th;
+            }
+            if (MODE != MODE_RECORD) {
+                f4 G = Dold;
+                if (MODE == MODE_EAGER) G = eager_gradient(d[j], p[j], Dold, sc);
+                outer_opt(a[j], u[j], G, sc);
+            }
+        }
+    if (MODE != MODE_RECORD) {
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j)
+            if (FULL || j < cnt) store4(theta + (m0 + j) * stride + i, a[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j)
+        if (FULL || j < cnt) store4(sv.a(m0 + j, i), a[j]);
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j)
+        if (FULL || j < cnt) {
+            if (MODE != MODE_RECORD) store4(sv.u(m0 + j, i), u[j]);
+            store4(sv.p(m0 + j, i), sent(d[j], sc));
+        }
+}
+
+// STAGE: a_m and Delta_m wait in LDS between the passes (32 bytes per lane and replica; a lane
+// only reads back what it wrote itself, so no barrier), one wavefront per workgroup.  Otherwise
+// the second pass re-reads theta_m and a_m (2M of the 8M+2 accesses per index happen twice).
+template <typename TT, int MODE, typename SV, bool STAGE>
+__global__ __launch_bounds__(STAGE ? 64 : kMaxBlock) void outer_eager_grouped_kernel(
+    TT* __restrict__ theta, SV sv, int M, int64_t n, int64_t stride, OuterScalars sc, int64_t per_xcd) {
+    extern __shared__ f4 stage[];  // STAGE: [M][2][64]
     const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     const int64_t nvec = n >> 2;
     if (v >= nvec) {
@@ -302,36 +334,19 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_twopass_kernel(TT* __re
         return;
     }
     const int64_t i = v << 2;
+    const int tid = threadIdx.x;
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-#pragma unroll 4
-    for (int m = 0; m < M; ++m) {
-        const f4 q = sent(load4(sv.a(m, i)) - load4(theta + m * stride + i), sc);
-        s0 += (double)q.x;
-        s1 += (double)q.y;
-        s2 += (double)q.z;
-        s3 += (double)q.w;
-    }
+    int m0 = 0;
+    for (; m0 + kGroup <= M; m0 += kGroup)
+        group_reduce<TT, MODE, SV, true, STAGE>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, s0, s1, s2, s3);
+    if (m0 < M) group_reduce<TT, MODE, SV, false, STAGE>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, s0, s1, s2, s3);
     f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
                (float)(s3 * sc.inv_M_d)};
     f4 Dold = {0.f, 0.f, 0.f, 0.f};
     if (MODE != MODE_RECORD) Dold = load4(sv.d(i));
-    for (int m = 0; m < M; ++m) {
-        f4 an = load4(sv.a(m, i));
-        const f4 th = load4(theta + m * stride + i);
-        const f4 d = an - th;
-        if (MODE == MODE_RECORD) {
-            store4(sv.a(m, i), th);
-        } else {
-            f4 un = load4(sv.u(m, i));
-            f4 G = Dold;
-            if (MODE == MODE_EAGER) G = eager_gradient(d, load4(sv.p(m, i)), Dold, sc);
-            outer_opt(an, un, G, sc);
-            store4(theta + m * stride + i, an);
-            store4(sv.a(m, i), an);
-            store4(sv.u(m, i), un);
-        }
-        store4(sv.p(m, i), sent(d, sc));
-    }
+    for (m0 = 0; m0 + kGroup <= M; m0 += kGroup)
+        group_update<TT, MODE, SV, true, STAGE>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
+    if (m0 < M) group_update<TT, MODE, SV, false, STAGE>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
     store4(sv.d(i), dbar);
 }
 
@@ -545,23 +560,30 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
         default: break;
     }
 #undef DILOCO_REG_CASE
-    // Other M.  LDS staging (32 bytes per thread and replica, one wavefront per workgroup) while
-    // at least kMinStagedWaves such workgroups fit a CU's 160 KB; beyond that the two-pass kernel.
-    const int64_t lds = (int64_t)64 * 32 * M;
-    const int path = tuning().generic_path;  // 0: choose, 1: LDS, 2: two-pass
-    if ((path == 0 && lds * kMinStagedWaves <= kLdsPerCu) || (path == 1 && lds <= kLdsPerCu)) {
-        if (lds > 48 * 1024 &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&outer_eager_lds_kernel<TT, MODE, SV>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return DILOCO_ERR_LAUNCH;
+    // Other M.  LDS staging (32 bytes per lane and replica, one wavefront per workgroup) while
+    // kMinStagedWaves such workgroups fit a CU's 160 KB (M <= 40); beyond that the two-pass kernel.
+    // Left to themselves they run with at most 3 resp. 2 one-wavefront workgroups per CU (measured
+    // best: 6.3-6.6 TB/s staged, 5.3-5.5 two-pass, of algorithmic bytes).  The cap may ask for more
+    // LDS than the staging needs, never less.
+    const Tuning& t = tuning();
+    const int64_t need = (int64_t)64 * 32 * M;
+    const bool staged = (t.generic_path == 0 && need * kMinStagedWaves <= kLdsPerCu) ||
+                        (t.generic_path == 1 && need <= kLdsPerCu);
+    const int cap = t.wg_per_cu >= 0 ? t.wg_per_cu : (t.block ? 0 : (staged ? 3 : 2));
+    int64_t cap_lds = cap > 0 ? kLdsPerCu / cap : 0;
+    cap_lds -= cap_lds % 1280;
+    if (staged) {
+        const size_t lds = (size_t)(need > cap_lds ? need : cap_lds);
+        if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV, true>, lds)) return DILOCO_ERR_LAUNCH;
         Grid g = make_grid(threads, 64);
-        hipLaunchKernelGGL((outer_eager_lds_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(64), (size_t)lds, st,
+        hipLaunchKernelGGL((outer_eager_grouped_kernel<TT, MODE, SV, true>), dim3(g.blocks), dim3(64), lds, st,
                            theta, sv, M, n, stride, sc, g.per_xcd);
         return launch_status();
     }
+    if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV, false>, (size_t)cap_lds)) return DILOCO_ERR_LAUNCH;
     Grid g = make_grid(threads, block);
-    hipLaunchKernelGGL((outer_eager_twopass_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(block), 0, st, theta,
-                       sv, M, n, stride, sc, g.per_xcd);
+    hipLaunchKernelGGL((outer_eager_grouped_kernel<TT, MODE, SV, false>), dim3(g.blocks), dim3(block),
+                       (size_t)cap_lds, st, theta, sv, M, n, stride, sc, g.per_xcd);
     return launch_status();
 }
 

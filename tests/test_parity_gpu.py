@@ -108,7 +108,7 @@ def test_eager_large_M_paths_agree_bitwise():
         assert torch.equal(a[k][..., :n], b[k][..., :n]), k
 
 
-@pytest.mark.parametrize("M", [9, 12, 16, 40])
+@pytest.mark.parametrize("M", [9, 12, 16, 40, 41, 80])
 def test_eager_generic_paths_agree_bitwise(M):
     """Replica counts without a register instantiation run LDS-staged or two-pass; both promise
     the arithmetic of the register kernel in the same order."""
