@@ -236,8 +236,9 @@ extern "C" int diloco_sim_quadratic_inner(float* theta, float* m1, float* m2, in
     if (n == 0) return DILOCO_OK;
     const AdamScalars sc = make_adam(lr, beta1, beta2, eps, weight_decay, step);
     const uint64_t k0 = mix64(seed + kGolden * (uint64_t)(step + 1));
-    // a wavefront loads h, theta* and theta, m1, m2 of every replica, 16 B a lane each
-    const Shape shape = launch_shape((int64_t)64 * 16 * (2 + 3 * M), 64 * 1024);
+    // the kernel walks the replicas one at a time: a wavefront has h, theta* and one replica's
+    // theta, m1, m2 in flight, 16 B a lane each (measured best at M = 4: 12 workgroups per CU)
+    const Shape shape = launch_shape((int64_t)64 * 16 * 5, 64 * 1024);
     const int block = shape.block;
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;

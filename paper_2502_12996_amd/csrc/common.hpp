@@ -92,12 +92,19 @@ constexpr int kLdsPerCu = 160 * 1024;  // gfx950
 // 5.8 -> 6.4 TB/s at M = 8).  The throttle is dynamic LDS the kernel never touches, sized so that
 // only `cap` workgroups fit a CU's 160 KB.  Left to itself (block 0, wg_per_cu -1) a launch uses
 // one-wavefront workgroups and as many of them per CU as bring `target_bytes` of loads in flight,
-// given that a wavefront issues `wave_load_bytes` before its first store (at least 2; no throttle
-// from 32 up).  An explicit block size switches the throttle off unless wg_per_cu is set too.
+// given that a wavefront issues `wave_load_bytes` before its first store (at least 2; from 4 up a
+// multiple of 4, one SIMD's share each; no throttle from 32 up).  An explicit block size switches the throttle off unless wg_per_cu is set too.
 struct Shape {
     int block;
     size_t lds;
 };
+// Smallest dynamic LDS size of which cap + 1 workgroups no longer fit a CU (0: no cap), so that at
+// most `cap` are resident whatever the allocation granule.
+inline size_t cap_lds_bytes(int cap) {
+    if (cap <= 0) return 0;
+    const size_t b = (size_t)kLdsPerCu / (size_t)(cap + 1) + 1;
+    return (b + 255) & ~(size_t)255;
+}
 inline Shape launch_shape(int64_t wave_load_bytes, int64_t target_bytes) {
     const Tuning& t = tuning();
     Shape s{t.block ? t.block : 64, 0};
@@ -106,13 +113,11 @@ inline Shape launch_shape(int64_t wave_load_bytes, int64_t target_bytes) {
         cap = 0;
         if (!t.block) {
             cap = (int)((target_bytes + wave_load_bytes - 1) / wave_load_bytes);
+            if (cap >= 4) cap = (cap + 2) / 4 * 4;  // the same number of wavefronts on each of the 4 SIMDs
             cap = cap < 2 ? 2 : (cap >= 32 ? 0 : cap);
         }
     }
-    if (cap > 0) {
-        s.lds = (size_t)(kLdsPerCu / cap);
-        s.lds -= s.lds % 1280;
-    }
+    s.lds = cap_lds_bytes(cap);
     return s;
 }
 // Workgroup size of the kernels that take no throttle.

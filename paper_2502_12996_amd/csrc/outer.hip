@@ -548,7 +548,7 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
                            shape.lds, st, theta, sv, n, stride, sc, g.per_xcd);                           \
         return launch_status();                                                                           \
     }
-    switch (M) {
+    switch (tuning().generic_path ? 0 : M) {  // a forced generic path also replaces the register kernels
         DILOCO_REG_CASE(1)
         DILOCO_REG_CASE(2)
         DILOCO_REG_CASE(3)
@@ -570,8 +570,7 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
     const bool staged = (t.generic_path == 0 && need * kMinStagedWaves <= kLdsPerCu) ||
                         (t.generic_path == 1 && need <= kLdsPerCu);
     const int cap = t.wg_per_cu >= 0 ? t.wg_per_cu : (t.block ? 0 : (staged ? 3 : 2));
-    int64_t cap_lds = cap > 0 ? kLdsPerCu / cap : 0;
-    cap_lds -= cap_lds % 1280;
+    const int64_t cap_lds = (int64_t)cap_lds_bytes(cap);
     if (staged) {
         const size_t lds = (size_t)(need > cap_lds ? need : cap_lds);
         if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV, true>, lds)) return DILOCO_ERR_LAUNCH;
