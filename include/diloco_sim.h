@@ -69,8 +69,9 @@ int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream
  *                  (1..32; enforced with dynamic LDS the kernel never touches); 0: no cap; -1 (the
  *                  default): with "block" 0 the launch picks the cap that puts about 32-64 KB of
  *                  loads in flight per compute unit, with an explicit "block" there is no cap.
- *   "generic_path" eager kernel for replica counts without a register instantiation: 0 = choose,
- *                  1 = LDS-staged, 2 = two-pass.
+ *   "generic_path" 0 = the eager entry points choose their kernel (register-resident for M <= 8,
+ *                  LDS-staged for M <= 40, two-pass beyond); 1 = LDS-staged for every M it can hold
+ *                  (M <= 80), 2 = two-pass for every M.
  * Results do not depend on any of them.
  * Returns DILOCO_OK or DILOCO_ERR_HYPER for an unknown key / value.  Not thread safe.
  */

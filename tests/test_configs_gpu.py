@@ -300,7 +300,7 @@ def test_quadratic_forty_phases(variant, lr_div):
           f"loss deviation {worst_loss:.2e}, worst state error after {H * wl.phases} steps {worst_state:.2e}")
 
 
-@pytest.mark.parametrize("block,xcd,cap", [(0, 0, -1), (256, 0, 0), (64, 1, 3), (512, 1, 0)])
+@pytest.mark.parametrize("block,xcd,cap", [(0, 0, -1), (256, 0, 0), (64, 1, 3), (512, 1, 0), (256, 1, 1), (64, 0, 2)])
 def test_t550m_packed_state_eager_outer_step_per_call(block, xcd, cap):
     """Config 3 through the packed-state entry point, in launch shapes the benchmark picks from."""
     wl = W.WORKLOADS["t550m"]
