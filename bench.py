@@ -265,6 +265,27 @@ def main():
                                     "launch": shape_json(shape_sync)}
     del sa, sv
 
+    # the stand-in training problem (configuration 5's shape): one inner step with the gradient made
+    # in the kernel (HBM-bound), and a whole phase of H steps in one pass (vector-ALU-bound)
+    set_shape(shape_default)
+    ql = W.WORKLOADS["quadratic"]
+    qt = torch.zeros((ql.M, ql.n), dtype=torch.float32, device=dev)
+    q1, q2 = torch.zeros_like(qt), torch.zeros_like(qt)
+    qh = W.log_uniform((ql.n,), 1e-3, 1.0, tag="h", device=dev)
+    qs = W.normal((ql.n,), 1.0, tag="theta_star", device=dev)
+    qkw = dict(noise_std=ql.noise_std, seed=W.BASE_SEED, lr=ql.lr, beta1=ql.beta1, beta2=ql.beta2, eps=ql.eps,
+               weight_decay=ql.weight_decay)
+    for t in range(1, 21):      # leave the all-zero start behind
+        d.sim_quadratic_inner(qt, q1, q2, qh, qs, step=t, **qkw)
+    q_ms = timed(lambda: d.sim_quadratic_inner(qt, q1, q2, qh, qs, step=21, **qkw), 9)[4]
+    p_ms = timed(lambda: d.sim_quadratic_phase(qt, q1, q2, qh, qs, step_first=22, steps=ql.H, **qkw), 5)[2]
+    extra["quadratic_sim"] = {"M": ql.M, "n": ql.n, "inner_step_ms": q_ms,
+                              "inner_step_GBps": (8 + 24 * ql.M) * ql.n / (q_ms * 1e-3) / 1e9,
+                              "fused_phase_steps": ql.H, "fused_phase_ms": p_ms,
+                              "fused_replica_param_steps_per_s": ql.M * ql.n * ql.H / (p_ms * 1e-3),
+                              "fused_speedup_over_single_steps": ql.H * q_ms / p_ms}
+    del qt, q1, q2, qh, qs
+
     # practical ceiling: a plain copy kernel with the same access shape, in its best launch shape
     cbuf = torch.empty(2 * n, dtype=torch.float32, device=dev)
     src, dst = cbuf[:n], cbuf[n:]

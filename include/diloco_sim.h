@@ -38,6 +38,21 @@ int diloco_sim_quadratic_inner(float* theta, float* m1, float* m2,
                                double lr, double beta1, double beta2, double eps,
                                double weight_decay, int64_t step, void* stream);
 
+/*
+ * `steps` consecutive calls of diloco_sim_quadratic_inner, for step = step_first,
+ * step_first + 1, ..., in one pass: every replica's theta, m1, m2 are read once, stepped in
+ * registers and written once (legitimate for this separable stand-in problem only: a real
+ * model's gradient needs the whole parameter vector of the previous step).  The results are
+ * bit-identical to the separate calls.  0 <= steps <= DILOCO_SIM_MAX_FUSED_STEPS (longer
+ * phases take several calls); the other arguments are those of diloco_sim_quadratic_inner.
+ */
+#define DILOCO_SIM_MAX_FUSED_STEPS 64
+int diloco_sim_quadratic_phase(float* theta, float* m1, float* m2, int M, int64_t n,
+                               int64_t stride, const float* h, const float* theta_star,
+                               double noise_std, uint64_t seed, int64_t index_base,
+                               double lr, double beta1, double beta2, double eps,
+                               double weight_decay, int64_t step_first, int steps, void* stream);
+
 /* Number of fp64 partial sums diloco_sim_quadratic_loss needs for n elements. */
 int64_t diloco_sim_loss_workspace(int64_t n);
 

@@ -59,6 +59,9 @@ SIGNATURES = {
     "diloco_sim_quadratic_inner": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_int, _c_i64, _c_i64, _c_ptr,
                                             _c_ptr, _c_dbl, ctypes.c_uint64, _c_i64, _c_dbl, _c_dbl,
                                             _c_dbl, _c_dbl, _c_dbl, _c_i64, _c_ptr]),
+    "diloco_sim_quadratic_phase": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_int, _c_i64, _c_i64, _c_ptr,
+                                            _c_ptr, _c_dbl, ctypes.c_uint64, _c_i64, _c_dbl, _c_dbl,
+                                            _c_dbl, _c_dbl, _c_dbl, _c_i64, _c_int, _c_ptr]),
     "diloco_sim_loss_workspace": (_c_i64, [_c_i64]),
     "diloco_sim_quadratic_loss": (_c_int, [_c_ptr, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr,
                                            _c_i64, _c_ptr, _c_ptr]),
@@ -256,6 +259,21 @@ def sim_quadratic_inner(theta, m1, m2, h, theta_star, *, n=None, noise_std, seed
     _check("diloco_sim_quadratic_inner", lib().diloco_sim_quadratic_inner(
         _ptr(theta), _ptr(m1), _ptr(m2), M, n, _row_stride(theta), _ptr(h), _ptr(theta_star),
         noise_std, seed, index_base, lr, beta1, beta2, eps, weight_decay, step, _stream(stream)))
+
+
+SIM_MAX_FUSED_STEPS = 64
+
+
+def sim_quadratic_phase(theta, m1, m2, h, theta_star, *, n=None, noise_std, seed, index_base=0,
+                        lr, beta1, beta2, eps, weight_decay, step_first, steps, stream=None) -> None:
+    """Steps step_first .. step_first + steps - 1 of sim_quadratic_inner in one pass
+    (steps <= SIM_MAX_FUSED_STEPS)."""
+    M = theta.shape[0]
+    n = theta.shape[1] if n is None else n
+    _check("diloco_sim_quadratic_phase", lib().diloco_sim_quadratic_phase(
+        _ptr(theta), _ptr(m1), _ptr(m2), M, n, _row_stride(theta), _ptr(h), _ptr(theta_star),
+        noise_std, seed, index_base, lr, beta1, beta2, eps, weight_decay, step_first, steps,
+        _stream(stream)))
 
 
 def sim_loss_workspace(n: int) -> int:

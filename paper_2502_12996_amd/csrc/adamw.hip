@@ -137,6 +137,70 @@ __global__ __launch_bounds__(kMaxBlock) void quadratic_inner_kernel(float* __res
     }
 }
 
+// The same steps for `steps` consecutive values of t in one pass (grid.y = replica): theta, m1, m2
+// are read once, stepped in registers and written once, which leaves the noise generator, the
+// square root and the division as the only cost: this kernel is bound by the vector ALU, not by
+// HBM.  Per element the arithmetic is the one of quadratic_inner_kernel in the same order.
+struct PhaseScalars {
+    float inv_bc1[DILOCO_SIM_MAX_FUSED_STEPS];  // 1 / (1 - beta1^t) for t = step_first + s
+    float inv_bc2[DILOCO_SIM_MAX_FUSED_STEPS];
+};
+
+__global__ __launch_bounds__(kMaxBlock) void quadratic_phase_kernel(
+    float* __restrict__ theta, float* __restrict__ m1, float* __restrict__ m2, const float* __restrict__ h,
+    const float* __restrict__ star, int64_t n, int64_t stride, float noise_std, uint64_t seed, int64_t step_first,
+    int steps, int64_t index_base, AdamScalars sc, PhaseScalars ps, int64_t per_xcd) {
+    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    const int64_t nvec = n >> 2;
+    if (v > nvec) return;
+    const int m = blockIdx.y;
+    if (v == nvec) {
+        for (int64_t e = n & ~(int64_t)3; e < n; ++e) {
+            const float hh = h[e], ss = star[e];
+            const uint64_t gi = (uint64_t)(index_base + e);
+            const int64_t i = m * stride + e;
+            float t = theta[i], a = m1[i], b = m2[i];
+            for (int s = 0; s < steps; ++s) {
+                const uint64_t k0 = mix64(seed + kGolden * (uint64_t)(step_first + s + 1));
+                const uint64_t key = mix64(k0 + kGolden * (uint64_t)(m + 1));
+                float z0, z1;
+                normal_pair(key, gi >> 1, z0, z1);
+                AdamScalars st = sc;
+                st.inv_bc1 = ps.inv_bc1[s];
+                st.inv_bc2 = ps.inv_bc2[s];
+                const float g = fmaf(noise_std, (gi & 1) ? z1 : z0, hh * (t - ss));
+                adamw_update(t, a, b, g, st);
+            }
+            theta[i] = t;
+            m1[i] = a;
+            m2[i] = b;
+        }
+        return;
+    }
+    const int64_t e = v << 2;
+    const f4 hh = *reinterpret_cast<const f4*>(h + e);
+    const f4 ss = *reinterpret_cast<const f4*>(star + e);
+    const uint64_t j = (uint64_t)(index_base + e) >> 1;
+    const int64_t i = m * stride + e;
+    f4 t = load4(theta + i), a = load4(m1 + i), b = load4(m2 + i);
+    for (int s = 0; s < steps; ++s) {
+        const uint64_t k0 = mix64(seed + kGolden * (uint64_t)(step_first + s + 1));
+        const uint64_t key = mix64(k0 + kGolden * (uint64_t)(m + 1));
+        float z0, z1, z2, z3;
+        normal_pair(key, j, z0, z1);
+        normal_pair(key, j + 1, z2, z3);
+        const f4 z = {z0, z1, z2, z3};
+        AdamScalars st = sc;
+        st.inv_bc1 = ps.inv_bc1[s];
+        st.inv_bc2 = ps.inv_bc2[s];
+        const f4 g = fma_(splat<f4>(noise_std), z, hh * (t - ss));
+        adamw_update(t, a, b, g, st);
+    }
+    store4(theta + i, t);
+    store4(m1 + i, a);
+    store4(m2 + i, b);
+}
+
 // ---------------------------------------------------------------- host side
 static int check_adam_hyper(double lr, double b1, double b2, double eps, double wd, int64_t step) {
     if (!is_finite(lr) || !in_unit(b1) || !in_unit(b2) || !is_finite(eps) || eps <= 0.0 ||
@@ -247,5 +311,45 @@ extern "C" int diloco_sim_quadratic_inner(float* theta, float* m1, float* m2, in
     hipLaunchKernelGGL(quadratic_inner_kernel, dim3(g.blocks), dim3(block), shape.lds,
                        static_cast<hipStream_t>(stream), theta, m1, m2, h, theta_star, M, n, stride,
                        (float)noise_std, k0, index_base, sc, g.per_xcd);
+    return launch_status();
+}
+
+extern "C" int diloco_sim_quadratic_phase(float* theta, float* m1, float* m2, int M, int64_t n,
+                                          int64_t stride, const float* h, const float* theta_star,
+                                          double noise_std, uint64_t seed, int64_t index_base,
+                                          double lr, double beta1, double beta2, double eps,
+                                          double weight_decay, int64_t step_first, int steps, void* stream) {
+    if (!theta || !m1 || !m2 || !h || !theta_star) return DILOCO_ERR_NULL;
+    if (int e = check_shape(M, n, stride)) return e;
+    if (index_base < 0 || (index_base & 3)) return DILOCO_ERR_SHAPE;
+    if (steps < 0 || steps > DILOCO_SIM_MAX_FUSED_STEPS) return DILOCO_ERR_SHAPE;
+    if (int e = check_adam_hyper(lr, beta1, beta2, eps, weight_decay, step_first)) return e;
+    if (step_first > ((int64_t)1 << 60)) return DILOCO_ERR_HYPER;
+    if (!is_finite(noise_std) || noise_std < 0.0) return DILOCO_ERR_HYPER;
+    if (!aligned_to(theta, 16) || !aligned_to(m1, 16) || !aligned_to(m2, 16) || !aligned_to(h, 16) ||
+        !aligned_to(theta_star, 16) || (M > 1 && stride % 4 != 0))
+        return DILOCO_ERR_ALIGN;
+    Range r[5] = {{theta, extent_bytes(M, n, stride, 4), true},
+                  {m1, extent_bytes(M, n, stride, 4), true},
+                  {m2, extent_bytes(M, n, stride, 4), true},
+                  {h, n * 4, false},
+                  {theta_star, n * 4, false}};
+    if (int e = check_alias(r, 5)) return e;
+    if (n == 0 || steps == 0) return DILOCO_OK;
+    const AdamScalars sc = make_adam(lr, beta1, beta2, eps, weight_decay, step_first);
+    PhaseScalars ps;
+    for (int s = 0; s < DILOCO_SIM_MAX_FUSED_STEPS; ++s) {
+        const AdamScalars one = make_adam(lr, beta1, beta2, eps, weight_decay, step_first + (s < steps ? s : 0));
+        ps.inv_bc1[s] = one.inv_bc1;
+        ps.inv_bc2[s] = one.inv_bc2;
+    }
+    // bound by the vector ALU: full occupancy, no throttle
+    const int block = plain_block();
+    const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
+    if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
+    Grid g = make_grid(threads, block);
+    hipLaunchKernelGGL(quadratic_phase_kernel, dim3(g.blocks, M), dim3(block), 0,
+                       static_cast<hipStream_t>(stream), theta, m1, m2, h, theta_star, n, stride,
+                       (float)noise_std, seed, step_first, steps, index_base, sc, ps, g.per_xcd);
     return launch_status();
 }

@@ -4,6 +4,8 @@ The outer loop of Algorithms 1-3 (`for t = 1..T`, `if t mod H == 0`) is host con
 lives here; every arithmetic step runs in the library's kernels:
 
     lines 3-5   diloco_sim_quadratic_inner   (gradient made in registers + AdamW, all replicas)
+                diloco_sim_quadratic_phase   (the same for all steps between two boundaries in one
+                                              pass; --fused 1)
     lines 7-12  diloco_outer_sync / diloco_outer_eager / diloco_outer_eager_packed
     loss        diloco_sim_quadratic_loss    (at the replica mean of the outer parameters)
 
@@ -28,14 +30,16 @@ class QuadraticSimulation:
     three outer rules outside.  variant: "standard" (Algorithm 1), "delayed" (Algorithm 2),
     "eager" (Algorithm 3).  layout: "packed" or "rows" (outer state of Algorithms 2/3).
     fragments: Streaming-DiLoCo windows [(offset, count), ...] on staggered boundaries.
-    overlap: 1 (the listings) or 2 (2-outer-steps overlap; rows layout only)."""
+    overlap: 1 (the listings) or 2 (2-outer-steps overlap; rows layout only).
+    fused: run the inner steps between two outer boundaries as one pass over the buffers
+    (bit-identical to the step-by-step run)."""
 
     def __init__(self, M: int, n: int, H: int, variant: str = "eager", *, layout: str = "packed",
                  fragments: Optional[Sequence[Tuple[int, int]]] = None, overlap: int = 1,
                  comm_bf16: bool = False, comm_flags: int = 0, seed: int = W.BASE_SEED, noise_std: float = 0.1,
                  lr: float = 4e-4, beta1: float = 0.9, beta2: float = 0.95, eps: float = 1e-8,
                  weight_decay: float = 0.0, outer_lr: float = 0.7, outer_momentum: float = 0.9,
-                 nesterov: bool = True, device: str = "cuda:0"):
+                 nesterov: bool = True, fused: bool = False, device: str = "cuda:0"):
         assert variant in ("standard", "delayed", "eager")
         assert layout in ("packed", "rows") and overlap in (1, 2)
         self.M, self.n, self.H, self.variant = M, n, H, variant
@@ -48,6 +52,7 @@ class QuadraticSimulation:
         self.outer = dict(outer_lr=outer_lr, outer_momentum=outer_momentum, nesterov=nesterov)
         self.flags = ((B.DELAYED if variant == "delayed" else B.EAGER) | (B.COMM_BF16 if comm_bf16 else 0)
                       | comm_flags)      # comm_flags: e.g. binding.COMM_EXMY(2, 1, 11)
+        self.fused = fused
         self.t = 0
         f32 = dict(dtype=torch.float32, device=device)
         ns = (n + 3) & ~3                         # replica rows 16-byte aligned
@@ -71,9 +76,24 @@ class QuadraticSimulation:
         """Lines 3-5 for every replica, then the outer step of every fragment whose boundary this
         is.  Returns True if any outer boundary fell on this step."""
         self.t += 1
+        B.sim_quadratic_inner(self.theta, self.m1, self.m2, self.h, self.star, n=self.n,
+                              noise_std=self.noise_std, seed=self.seed, step=self.t, **self.adam)
+        return self._boundaries()
+
+    def advance(self, steps: int) -> bool:
+        """`steps` inner steps in as few passes as the library allows, then the outer steps due at
+        the step reached.  The caller makes sure no boundary falls strictly inside (run() does)."""
+        while steps > 0:
+            c = min(steps, B.SIM_MAX_FUSED_STEPS)
+            B.sim_quadratic_phase(self.theta, self.m1, self.m2, self.h, self.star, n=self.n,
+                                  noise_std=self.noise_std, seed=self.seed, step_first=self.t + 1, steps=c,
+                                  **self.adam)
+            self.t += c
+            steps -= c
+        return self._boundaries()
+
+    def _boundaries(self) -> bool:
         t, M, n, H = self.t, self.M, self.n, self.H
-        B.sim_quadratic_inner(self.theta, self.m1, self.m2, self.h, self.star, n=n,
-                              noise_std=self.noise_std, seed=self.seed, step=t, **self.adam)
         F = len(self.fragments)
         fired = False
         for f, (off, cnt) in enumerate(self.fragments):
@@ -109,8 +129,17 @@ class QuadraticSimulation:
     def run(self, phases: int) -> List[float]:
         """phases * H steps; the loss after every step on which an outer boundary fell."""
         losses = []
-        for _ in range(phases * self.H):
-            if self.step():
+        end = self.t + phases * self.H
+        while self.t < end:
+            if self.fused:
+                # up to the next step on which any fragment has a boundary
+                F = len(self.fragments)
+                nxt = next(t for t in range(self.t + 1, end + 1)
+                           if t == end or any(B.stream_due(t, self.H, F, f) for f in range(F)))
+                fired = self.advance(nxt - self.t)
+            else:
+                fired = self.step()
+            if fired:
                 losses.append(self.loss())
         torch.cuda.synchronize()
         return [float(x.item()) for x in losses]
@@ -124,11 +153,12 @@ def main() -> None:
     ap.add_argument("--H", type=int, default=wl.H)
     ap.add_argument("--phases", type=int, default=wl.phases)
     ap.add_argument("--layout", choices=("packed", "rows"), default="packed")
+    ap.add_argument("--fused", type=int, default=0, help="1: inner steps between boundaries in one pass")
     args = ap.parse_args()
     runs = [("standard", 1.0), ("eager", 1.0), ("delayed", 1.0), ("delayed", 0.25)]
     for variant, scale in runs:
         sim = QuadraticSimulation(args.M, args.n, args.H, variant, layout=args.layout,
-                                  noise_std=wl.noise_std, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2,
+                                  fused=bool(args.fused), noise_std=wl.noise_std, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2,
                                   eps=wl.eps, weight_decay=wl.weight_decay,
                                   outer_lr=wl.outer_lr * scale, outer_momentum=wl.outer_momentum)
         torch.cuda.synchronize()
@@ -136,7 +166,7 @@ def main() -> None:
         losses = sim.run(args.phases)
         dt = time.perf_counter() - t0
         print(json.dumps({"variant": variant, "outer_lr": wl.outer_lr * scale, "M": args.M, "n": args.n,
-                          "H": args.H, "phases": args.phases, "seconds": dt,
+                          "H": args.H, "phases": args.phases, "fused": args.fused, "seconds": dt,
                           "inner_steps_per_s": args.phases * args.H / dt, "loss": losses}), flush=True)
         del sim
         torch.cuda.empty_cache()

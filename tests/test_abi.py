@@ -167,6 +167,16 @@ def test_sim_validation_and_tuning(lib):
     assert q(base=2) == B.ERR_SHAPE
     assert q(noise=-1.0) == B.ERR_HYPER
     assert q(th=P[0] + 4) == B.ERR_ALIGN
+
+    def ph(th=P[0], m1=P[1], m2=P[2], M=2, n=64, stride=64, h=P[3], star=P[4], noise=0.1, base=0, first=1, steps=8):
+        return lib.diloco_sim_quadratic_phase(th, m1, m2, M, n, stride, h, star, noise, 1, base,
+                                              4e-4, 0.9, 0.95, 1e-8, 0.0, first, steps, None)
+    assert ph(n=0) == B.OK and ph(steps=0) == B.OK
+    assert ph(m2=None) == B.ERR_NULL
+    assert ph(steps=65) == B.ERR_SHAPE and ph(steps=-1) == B.ERR_SHAPE and ph(base=6) == B.ERR_SHAPE
+    assert ph(first=0) == B.ERR_HYPER and ph(noise=float("nan")) == B.ERR_HYPER
+    assert ph(star=P[4] + 8) == B.ERR_ALIGN and ph(stride=66) == B.ERR_ALIGN
+    assert ph(m1=P[0]) == B.ERR_ALIAS
     assert lib.diloco_sim_loss_workspace(0) == 1
     assert lib.diloco_sim_loss_workspace(1 << 26) == 8192
     assert lib.diloco_sim_quadratic_loss(P[0], 2, 64, 64, P[1], P[2], P[3], 0, P[4], None) == B.ERR_SHAPE

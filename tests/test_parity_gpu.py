@@ -297,6 +297,54 @@ def test_quadratic_inner_step_and_loss(M, n, base):
     assert abs(out.item() - want) <= 1e-12 * max(want, 1e-300)
 
 
+@pytest.mark.parametrize("M,n,base,first,steps", [(1, 7, 0, 1, 5), (4, 4099, 0, 1, 50), (3, 1 << 14, 1 << 26, 51, 64),
+                                                   (2, 1001, (1 << 33) + 4, 1999, 1), (2, 70_001, 8, 3, 0)])
+def test_quadratic_fused_phase_equals_separate_steps_bitwise(M, n, base, first, steps):
+    """One pass over `steps` inner steps in registers against the same steps launched one by one
+    (which the tests above hold to the checker step by step), and against the checker directly."""
+    wl = W.WORKLOADS["quadratic"]
+    h = W.log_uniform((n,), 1e-3, 1.0, tag="h", seed=39)
+    star = W.normal((n,), 1.0, tag="theta_star", seed=39)
+    ns = (n + 3) & ~3
+    th = W.normal((M, ns), 0.5, tag="theta", seed=39)
+    m1 = W.normal((M, ns), 0.1, tag="m1", seed=39)
+    m2 = W.normal((M, ns), 0.1, tag="m2", seed=39).square_()
+    kw = dict(n=n, noise_std=wl.noise_std, seed=0xBEEF, index_base=base, lr=wl.lr, beta1=wl.beta1,
+              beta2=wl.beta2, eps=wl.eps, weight_decay=0.0)
+    a = [x.to(DEV) for x in (th, m1, m2)]
+    b = [x.to(DEV) for x in (th, m1, m2)]
+    gh, gs = h.to(DEV), star.to(DEV)
+    for t in range(first, first + steps):
+        d.sim_quadratic_inner(*a, gh, gs, step=t, **kw)
+    d.sim_quadratic_phase(*b, gh, gs, step_first=first, steps=steps, **kw)
+    torch.cuda.synchronize()
+    for x, y, name in zip(a, b, ("theta", "m1", "m2")):
+        assert torch.equal(x, y), name
+    assert torch.equal(b[0][:, n:].cpu(), th[:, n:])
+    if steps and n <= 5000:
+        rt, r1, r2 = (W.to_f64(x[:, :n]) for x in (th, m1, m2))
+        rh, rs = W.to_f64(h), W.to_f64(star)
+        for t in range(first, first + steps):
+            O.quadratic_inner_step(rt, r1, r2, rh, rs, t, 0xBEEF, wl.noise_std, wl.lr, wl.beta1, wl.beta2,
+                                   wl.eps, 0.0, index_base=base)
+        # per-step differences of a few 1e-7 (fp32 log / sincos in the noise) add up over the steps
+        tol = TOL_F32 * max(1, steps) ** 0.5 * 2
+        assert_close(W.to_f64(b[0][:, :n]), rt, tol, "theta after the phase")
+        assert_close(W.to_f64(b[1][:, :n]), r1, tol, "m1 after the phase")
+        assert_close(W.to_f64(b[2][:, :n]), r2, tol, "m2 after the phase")
+
+
+def test_quadratic_fused_phase_rejects_too_many_steps():
+    z = torch.zeros((2, 64), device=DEV)
+    v = torch.ones(64, device=DEV)
+    with pytest.raises(d.DilocoError) as ei:
+        d.sim_quadratic_phase(z, z.clone(), z.clone(), v, v.clone(), noise_std=0.1, seed=1, lr=4e-4, beta1=0.9,
+                              beta2=0.95, eps=1e-8, weight_decay=0.0, step_first=1,
+                              steps=d.binding.SIM_MAX_FUSED_STEPS + 1)
+    assert ei.value.status == d.binding.ERR_SHAPE
+    assert not z.any()
+
+
 # ------------------------------------------------------------------ packed (tile-interleaved) outer state
 def _rows(M, n, seed, bf16=False, pad=0):
     return {k: v.to(DEV) for k, v in W.outer_state(wl_for(M, n, bf16), n, seed=seed, stride=n + pad).items()}

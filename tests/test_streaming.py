@@ -217,3 +217,22 @@ def test_resume_from_copied_buffers_is_bit_identical(variant, layout):
     for name in names:
         assert torch.equal(getattr(resumed, name), getattr(whole, name)), name
     assert torch.equal(resumed.loss(), whole.loss())
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant,layout,frags,H", [("eager", "packed", 1, 70), ("standard", "rows", 1, 5),
+                                                    ("eager", "rows", 3, 7), ("delayed", "packed", 2, 130)])
+def test_fused_inner_phases_give_the_step_by_step_run_bit_for_bit(variant, layout, frags, H):
+    """The driver's fused mode sweeps all inner steps up to the next boundary of any fragment in
+    one pass (several passes beyond 64 steps); nothing else changes, so every buffer and every
+    loss must equal the step-by-step run exactly."""
+    from paper_2502_12996_amd.simulate import QuadraticSimulation
+    n = 3 * 8192 + 4 * 17 + (0 if frags > 1 else 3)
+    fr = None if frags == 1 else [(k * 8192, 8192) for k in range(frags - 1)] + [((frags - 1) * 8192, n - (frags - 1) * 8192)]
+    kw = dict(M=3, n=n, H=H, variant=variant, layout=layout, fragments=fr, lr=1e-2)
+    slow, fast = QuadraticSimulation(**kw), QuadraticSimulation(fused=True, **kw)
+    l_slow, l_fast = slow.run(3), fast.run(3)
+    assert l_slow == l_fast and len(l_slow) == 3 * frags and slow.t == fast.t == 3 * H
+    names = ["theta", "m1", "m2"] + (["state"] if slow.packed else ["anchor", "vel"])
+    for name in names:
+        assert torch.equal(getattr(slow, name), getattr(fast, name)), name
