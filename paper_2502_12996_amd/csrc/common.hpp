@@ -122,12 +122,13 @@ inline Shape launch_shape(int64_t wave_load_bytes, int64_t target_bytes) {
 }
 // Workgroup size of the kernels that take no throttle.
 inline int plain_block() { return tuning().block ? tuning().block : 256; }
-// More than 48 KB of dynamic LDS has to be granted per kernel; false if the runtime refuses.
+// More than 48 KB of dynamic LDS has to be granted per kernel, once: the largest size granted so
+// far is remembered per kernel, so that a launch in steady state makes no runtime call besides
+// the launch itself.  false if the runtime refuses.
+bool grant_lds_for(const void* kernel, size_t lds);
 template <typename K>
 inline bool grant_lds(K kernel, size_t lds) {
-    if (lds <= 48 * 1024) return true;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)lds) == hipSuccess;
+    return lds <= 48 * 1024 || grant_lds_for(reinterpret_cast<const void*>(kernel), lds);
 }
 
 struct Range {

@@ -1,6 +1,8 @@
 // Loss of the quadratic stand-in problem (deterministic two-stage fp64 reduction),
 // launch tuning, status strings.
 #include <cstring>
+#include <mutex>
+#include <unordered_map>
 
 #include "common.hpp"
 #include "diloco_sim.h"
@@ -10,6 +12,20 @@ namespace diloco {
 Tuning& tuning() {
     static Tuning t;
     return t;
+}
+
+bool grant_lds_for(const void* kernel, size_t lds) {
+    static std::mutex lock;
+    static std::unordered_map<const void*, size_t> granted;
+    std::lock_guard<std::mutex> hold(lock);
+    size_t& have = granted[kernel];
+    if (lds <= have) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    have = lds;
+    return true;
 }
 
 constexpr int kLossBlock = 256;
