@@ -85,8 +85,8 @@ int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream
  *                  default): with "block" 0 the launch picks the cap that puts about 32-64 KB of
  *                  loads in flight per compute unit, with an explicit "block" there is no cap.
  *   "generic_path" 0 = the eager entry points choose their kernel (register-resident for M <= 8,
- *                  LDS-staged for M <= 40, two-pass beyond); 1 = LDS-staged for every M it can hold
- *                  (M <= 80), 2 = two-pass for every M.
+ *                  beyond that the first 40 replicas staged in LDS and the rest read twice);
+ *                  1 = for every M, up to 80 replicas staged; 2 = for every M, none staged.
  * Results do not depend on any of them.
  * Returns DILOCO_OK or DILOCO_ERR_HYPER for an unknown key / value.  Not thread safe.
  */

@@ -320,14 +320,16 @@ __device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& s
         }
 }
 
-// STAGE: a_m and Delta_m wait in LDS between the passes (32 bytes per lane and replica; a lane
-// only reads back what it wrote itself, so no barrier), one wavefront per workgroup.  Otherwise
-// the second pass re-reads theta_m and a_m (2M of the 8M+2 accesses per index happen twice).
-template <typename TT, int MODE, typename SV, bool STAGE>
-__global__ __launch_bounds__(STAGE ? 64 : kMaxBlock) void outer_eager_grouped_kernel(
-    TT* __restrict__ theta, SV sv, int M, int64_t n, int64_t stride, OuterScalars sc, int64_t per_xcd) {
-    extern __shared__ f4 stage[];  // STAGE: [M][2][64]
-    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+// The first `staged` replicas (a multiple of kGroup, or all M) keep a_m and Delta_m in LDS between
+// the passes (32 bytes per lane and replica; a lane only reads back what it wrote itself, so no
+// barrier); for the others the second pass re-reads theta_m and a_m (2 of their 8 accesses per
+// index happen twice).  One wavefront per workgroup.
+template <typename TT, int MODE, typename SV>
+__global__ __launch_bounds__(64) void outer_eager_grouped_kernel(TT* __restrict__ theta, SV sv, int M, int staged,
+                                                                 int64_t n, int64_t stride, OuterScalars sc,
+                                                                 int64_t per_xcd) {
+    extern __shared__ f4 stage[];  // [staged][2][64]
+    const int64_t v = logical_block(per_xcd) * 64 + threadIdx.x;
     const int64_t nvec = n >> 2;
     if (v >= nvec) {
         if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, M, n, stride, sc);
@@ -337,16 +339,34 @@ __global__ __launch_bounds__(STAGE ? 64 : kMaxBlock) void outer_eager_grouped_ke
     const int tid = threadIdx.x;
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
     int m0 = 0;
-    for (; m0 + kGroup <= M; m0 += kGroup)
-        group_reduce<TT, MODE, SV, true, STAGE>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, s0, s1, s2, s3);
-    if (m0 < M) group_reduce<TT, MODE, SV, false, STAGE>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, s0, s1, s2, s3);
+    for (; m0 + kGroup <= M; m0 += kGroup) {
+        if (m0 < staged)
+            group_reduce<TT, MODE, SV, true, true>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, s0, s1, s2, s3);
+        else
+            group_reduce<TT, MODE, SV, true, false>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, s0, s1, s2, s3);
+    }
+    if (m0 < M) {
+        if (m0 < staged)
+            group_reduce<TT, MODE, SV, false, true>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, s0, s1, s2, s3);
+        else
+            group_reduce<TT, MODE, SV, false, false>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, s0, s1, s2, s3);
+    }
     f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
                (float)(s3 * sc.inv_M_d)};
     f4 Dold = {0.f, 0.f, 0.f, 0.f};
     if (MODE != MODE_RECORD) Dold = load4(sv.d(i));
-    for (m0 = 0; m0 + kGroup <= M; m0 += kGroup)
-        group_update<TT, MODE, SV, true, STAGE>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
-    if (m0 < M) group_update<TT, MODE, SV, false, STAGE>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
+    for (m0 = 0; m0 + kGroup <= M; m0 += kGroup) {
+        if (m0 < staged)
+            group_update<TT, MODE, SV, true, true>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
+        else
+            group_update<TT, MODE, SV, true, false>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
+    }
+    if (m0 < M) {
+        if (m0 < staged)
+            group_update<TT, MODE, SV, false, true>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
+        else
+            group_update<TT, MODE, SV, false, false>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
+    }
     store4(sv.d(i), dbar);
 }
 
@@ -560,29 +580,25 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
         default: break;
     }
 #undef DILOCO_REG_CASE
-    // Other M.  LDS staging (32 bytes per lane and replica, one wavefront per workgroup) while
-    // kMinStagedWaves such workgroups fit a CU's 160 KB (M <= 40); beyond that the two-pass kernel.
-    // Left to themselves they run with at most 3 resp. 2 one-wavefront workgroups per CU (measured
-    // best: 6.3-6.6 TB/s staged, 5.3-5.5 two-pass, of algorithmic bytes).  The cap may ask for more
-    // LDS than the staging needs, never less.
+    // Other M: the grouped kernel, one wavefront per workgroup.  It stages as many replicas in LDS
+    // (2 KB each per workgroup) as leave room for kMinStagedWaves workgroups on a CU's 160 KB: all
+    // of them up to M = 40, the first 40 beyond; the rest are read twice.  generic_path 1 stages
+    // all that one workgroup per CU can hold (80), 2 stages none.  The kernel's 256 VGPRs and the
+    // staging already keep it to 4 workgroups per CU or fewer; left to itself a launch that stages
+    // nothing is capped at 2.  Measured, of algorithmic bytes: 6.2-6.6 TB/s fully staged (M <= 40),
+    // 6.2 / 5.8 / 5.6 at M = 48 / 64 / 80, 5.3-5.8 unstaged.  A cap may ask for more LDS than the
+    // staging needs, never less.
     const Tuning& t = tuning();
-    const int64_t need = (int64_t)64 * 32 * M;
-    const bool staged = (t.generic_path == 0 && need * kMinStagedWaves <= kLdsPerCu) ||
-                        (t.generic_path == 1 && need <= kLdsPerCu);
-    const int cap = t.wg_per_cu >= 0 ? t.wg_per_cu : (t.block ? 0 : (staged ? 3 : 2));
+    const int room = t.generic_path == 2 ? 0 : kLdsPerCu / (64 * 32) / (t.generic_path == 1 ? 1 : kMinStagedWaves);
+    const int staged = M <= room ? M : room / kGroup * kGroup;
+    const int64_t need = (int64_t)64 * 32 * staged;
+    const int cap = t.wg_per_cu >= 0 ? t.wg_per_cu : (staged ? 0 : 2);
     const int64_t cap_lds = (int64_t)cap_lds_bytes(cap);
-    if (staged) {
-        const size_t lds = (size_t)(need > cap_lds ? need : cap_lds);
-        if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV, true>, lds)) return DILOCO_ERR_LAUNCH;
-        Grid g = make_grid(threads, 64);
-        hipLaunchKernelGGL((outer_eager_grouped_kernel<TT, MODE, SV, true>), dim3(g.blocks), dim3(64), lds, st,
-                           theta, sv, M, n, stride, sc, g.per_xcd);
-        return launch_status();
-    }
-    if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV, false>, (size_t)cap_lds)) return DILOCO_ERR_LAUNCH;
-    Grid g = make_grid(threads, block);
-    hipLaunchKernelGGL((outer_eager_grouped_kernel<TT, MODE, SV, false>), dim3(g.blocks), dim3(block),
-                       (size_t)cap_lds, st, theta, sv, M, n, stride, sc, g.per_xcd);
+    const size_t lds = (size_t)(need > cap_lds ? need : cap_lds);
+    if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV>, lds)) return DILOCO_ERR_LAUNCH;
+    Grid g = make_grid(threads, 64);
+    hipLaunchKernelGGL((outer_eager_grouped_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(64), lds, st, theta, sv,
+                       M, staged, n, stride, sc, g.per_xcd);
     return launch_status();
 }
 

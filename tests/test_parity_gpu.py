@@ -108,13 +108,14 @@ def test_eager_large_M_paths_agree_bitwise():
         assert torch.equal(a[k][..., :n], b[k][..., :n]), k
 
 
-@pytest.mark.parametrize("M", [9, 12, 16, 40, 41, 80])
+@pytest.mark.parametrize("M", [9, 12, 16, 40, 41, 80, 83])
 def test_eager_generic_paths_agree_bitwise(M):
-    """Replica counts without a register instantiation run LDS-staged or two-pass; both promise
-    the arithmetic of the register kernel in the same order."""
+    """Replica counts without a register instantiation run the grouped kernel, which stages the
+    first 40 (generic_path 1: 80; 2: none) replicas in LDS and reads the others twice; every
+    split promises the arithmetic of the register kernel in the same order."""
     n = 20_003
     out = []
-    for path in (1, 2):
+    for path in (0, 1, 2):
         d.tune("generic_path", path)
         try:
             g = _rows(M, n, 71)
@@ -126,12 +127,13 @@ def test_eager_generic_paths_agree_bitwise(M):
             d.tune("generic_path", 0)
     for k in out[0]:
         assert torch.equal(out[0][k], out[1][k]), k
+        assert torch.equal(out[0][k], out[2][k]), k
     st = W.outer_state(wl_for(M, n), n, seed=71)
     ref = {k: W.to_f64(v) for k, v in st.items()}
     O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU,
                   True, True)
     for k in ref:
-        assert_close(W.to_f64(out[1][k]), ref[k], TOL_F32, f"two-pass M={M} {k}")
+        assert_close(W.to_f64(out[0][k]), ref[k], TOL_F32, f"grouped kernel M={M} {k}")
 
 
 def test_eager_empty_input_is_a_noop():
