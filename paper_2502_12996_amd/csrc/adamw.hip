@@ -226,7 +226,7 @@ template <typename PT, typename GT>
 static int launch_adamw(void* theta, void* m1, void* m2, const void* grad, int M, int64_t n,
                         int64_t stride, const AdamScalars& sc, bool vec_ok, hipStream_t st) {
     // a wavefront of the vector kernel loads theta, m1, m2 and the gradient of 256 parameters
-    const Shape shape = launch_shape((int64_t)64 * 4 * (3 * sizeof(PT) + sizeof(GT)), 32 * 1024);
+    const Shape shape = launch_shape((int64_t)64 * 4 * (3 * sizeof(PT) + sizeof(GT)), kInFlightTarget);
     const int block = shape.block;
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
@@ -301,7 +301,8 @@ extern "C" int diloco_sim_quadratic_inner(float* theta, float* m1, float* m2, in
     const AdamScalars sc = make_adam(lr, beta1, beta2, eps, weight_decay, step);
     const uint64_t k0 = mix64(seed + kGolden * (uint64_t)(step + 1));
     // the kernel walks the replicas one at a time: a wavefront has h, theta* and one replica's
-    // theta, m1, m2 in flight, 16 B a lane each (measured best at M = 4: 12 workgroups per CU)
+    // theta, m1, m2 in flight, 16 B a lane each; the noise generator keeps the ALU busy for long, so
+    // more wavefronts than for the plain sweeps pay (measured best at M = 4: 12 workgroups per CU)
     const Shape shape = launch_shape((int64_t)64 * 16 * 5, 64 * 1024);
     const int block = shape.block;
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);

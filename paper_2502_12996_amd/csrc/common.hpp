@@ -98,6 +98,9 @@ struct Shape {
     int block;
     size_t lds;
 };
+// Loads in flight per CU at which the streaming sweeps measured fastest (eager step M = 1..8 fp32
+// and bf16, standard step M = 1..64, AdamW): 30-50 KB.
+constexpr int64_t kInFlightTarget = 36 * 1024;
 // Smallest dynamic LDS size of which cap + 1 workgroups no longer fit a CU (0: no cap), so that at
 // most `cap` are resident whatever the allocation granule.
 inline size_t cap_lds_bytes(int cap) {

@@ -373,6 +373,24 @@ __global__ __launch_bounds__(64) void outer_eager_grouped_kernel(TT* __restrict_
 // ------------------------------------------------------------------ standard DiLoCo
 // Shared outer parameters: nothing per replica has to survive the reduction, so a runtime
 // loop over m suffices.
+// K consecutive replicas' theta at one index: all K loads first, then the sum in replica order.
+template <int K, typename TT>
+__device__ __forceinline__ void sync_group(const TT* __restrict__ th0, int64_t stride, f4 a, double& s0, double& s1,
+                                           double& s2, double& s3) {
+    static_assert(K <= kGroup, "group too large");
+    f4 th[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) th[j] = load4(th0 + j * stride);
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+        const f4 d = a - th[j];
+        s0 += (double)d.x;
+        s1 += (double)d.y;
+        s2 += (double)d.z;
+        s3 += (double)d.w;
+    }
+}
+
 template <typename TT>
 __global__ __launch_bounds__(kMaxBlock) void outer_sync_vec_kernel(TT* __restrict__ theta, float* __restrict__ anchor,
                                                                    float* __restrict__ vel,
@@ -399,13 +417,18 @@ __global__ __launch_bounds__(kMaxBlock) void outer_sync_vec_kernel(TT* __restric
     const int64_t i = v << 2;
     f4 a = load4(anchor + i), u = load4(vel + i);
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-#pragma unroll 8
-    for (int m = 0; m < M; ++m) {
-        f4 d = a - load4(theta + m * stride + i);
-        s0 += (double)d.x;
-        s1 += (double)d.y;
-        s2 += (double)d.z;
-        s3 += (double)d.w;
+    // replicas in groups of kGroup, a group's loads issued together; the sum runs over m = 0, 1, ...
+    int m0 = 0;
+    for (; m0 + kGroup <= M; m0 += kGroup) sync_group<kGroup>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3);
+    switch (M - m0) {
+        case 1: sync_group<1>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
+        case 2: sync_group<2>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
+        case 3: sync_group<3>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
+        case 4: sync_group<4>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
+        case 5: sync_group<5>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
+        case 6: sync_group<6>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
+        case 7: sync_group<7>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
+        default: break;
     }
     f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
                (float)(s3 * sc.inv_M_d)};
@@ -549,7 +572,7 @@ template <typename TT, int MODE, typename SV>
 static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, const OuterScalars& sc,
                         bool vec_ok, hipStream_t st) {
     // a wavefront of the vector kernels loads theta_m, a_m, u_m, P_m of every replica and D: 16 B a lane each
-    const Shape shape = launch_shape((int64_t)64 * ((3 * M + 1) * 16 + M * 4 * (int64_t)sizeof(TT)), 64 * 1024);
+    const Shape shape = launch_shape((int64_t)64 * ((3 * M + 1) * 16 + M * 4 * (int64_t)sizeof(TT)), kInFlightTarget);
     const int block = shape.block;
     if (!vec_ok) {
         if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
@@ -746,8 +769,10 @@ extern "C" int diloco_unpack_state(const float* state, int M, int64_t n, float* 
 template <typename TT>
 static int launch_sync(TT* theta, float* anchor, float* vel, float* mean_out, int M, int64_t n,
                        int64_t stride, const OuterScalars& sc, bool vec_ok, hipStream_t st) {
-    // a wavefront of the vector kernel loads theta_m of every replica, the anchor and the velocity
-    const Shape shape = launch_shape((int64_t)64 * (2 * 16 + M * 4 * (int64_t)sizeof(TT)), 64 * 1024);
+    // a wavefront of the vector kernel has the anchor, the velocity and one group of theta_m in
+    // flight; measured best (n = 2^26, fp32): 12 / 8 / 8 / 4 workgroups per CU at M = 1 / 2 / 4 / >= 8
+    const int grp = M < kGroup ? M : kGroup;
+    const Shape shape = launch_shape((int64_t)64 * (2 * 16 + grp * 4 * (int64_t)sizeof(TT)), kInFlightTarget);
     const int block = shape.block;
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;

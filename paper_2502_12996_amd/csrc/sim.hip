@@ -128,7 +128,7 @@ extern "C" int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, v
     Range r[2] = {{dst, n * 4, true}, {src, n * 4, false}};
     if (int e = check_alias(r, 2)) return e;
     if (n == 0) return DILOCO_OK;
-    const Shape shape = launch_shape(64 * 16, 64 * 1024);  // one load a lane: never throttled by itself
+    const Shape shape = launch_shape(64 * 16, kInFlightTarget);  // one load a lane: never throttled by itself
     const int block = shape.block;
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
