@@ -172,7 +172,8 @@ int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, int64_t n, 
 int64_t diloco_packed_state_elems(int M, int64_t n);
 
 /* rows -> packed.  anchor, vel, prev_local: [M][state_stride] fp32; prev_mean: [n] fp32;
- * any of the four may be NULL, its streams are then left as they are. */
+ * any of the four may be NULL, its streams are then left as they are.  The two conversions
+ * take 3M+1 <= 65535 (M <= 21844), DILOCO_ERR_SHAPE beyond. */
 int diloco_pack_state(float* state, int M, int64_t n, const float* anchor, const float* vel,
                       const float* prev_local, int64_t state_stride, const float* prev_mean,
                       void* stream);

@@ -136,6 +136,63 @@ def test_eager_generic_paths_agree_bitwise(M):
         assert_close(W.to_f64(out[0][k]), ref[k], TOL_F32, f"grouped kernel M={M} {k}")
 
 
+@pytest.mark.parametrize("M,n", [(1000, 37), (65535, 5)])
+def test_very_many_replicas(M, n):
+    """The largest replica count the ABI takes (and one in between): outer steps, AdamW and reset."""
+    wl = wl_for(M, n)
+    st = W.outer_state(wl, n, seed=89, stride=n + 3)
+    ref = {k: W.to_f64(v[..., :n]) for k, v in st.items()}
+    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU, True, True)
+    g = {k: v.to(DEV) for k, v in st.items()}
+    d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], n=n,
+                  outer_lr=ETA, outer_momentum=MU)
+    torch.cuda.synchronize()
+    for k in ref:
+        assert_close(W.to_f64(g[k][..., :n]), ref[k], TOL_F32, f"eager M={M} {k}")
+    if 3 * M + 1 <= 65535:
+        pk = {k: v.to(DEV) for k, v in st.items()}
+        state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+        d.pack_state(state, M, n, anchor=pk["anchor"], vel=pk["vel"], prev_local=pk["prev_local"],
+                     prev_mean=pk["prev_mean"])
+        d.outer_eager_packed(pk["theta"], state, n=n, outer_lr=ETA, outer_momentum=MU)
+        d.unpack_state(state, M, n, anchor=pk["anchor"], vel=pk["vel"], prev_local=pk["prev_local"],
+                       prev_mean=pk["prev_mean"])
+        torch.cuda.synchronize()
+        for k in g:
+            assert torch.equal(pk[k], g[k]), k
+    else:
+        with pytest.raises(d.DilocoError) as ei:
+            d.pack_state(torch.zeros(8, device=DEV), M, n, anchor=g["anchor"])
+        assert ei.value.status == d.binding.ERR_SHAPE
+    # standard outer step and reset
+    st = W.outer_state(wl, n, seed=97)
+    theta, a, u = st["theta"], st["anchor"][0].clone(), st["vel"][0].clone()
+    rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
+    O.outer_standard(rt, ra, ru, ETA, MU, True)
+    gt, ga, gu = theta.to(DEV), a.to(DEV), u.to(DEV)
+    d.outer_sync(gt, ga, gu, outer_lr=ETA, outer_momentum=MU)
+    th2 = torch.zeros_like(gt)
+    d.reset(th2, ga)
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(ga), ra, TOL_F32, f"sync anchor M={M}")
+    assert_close(W.to_f64(gu), ru, TOL_F32, f"sync vel M={M}")
+    assert torch.equal(gt, ga.expand(M, n)) and torch.equal(th2, gt)
+    # AdamW: grid.y = replica
+    ad = W.adamw_state(wl, n, seed=101)
+    refa = {k: W.to_f64(v) for k, v in ad.items()}
+    O.adamw_step(refa["theta"], refa["m1"], refa["m2"], refa["grad"], 3, 4e-4, 0.9, 0.95, 1e-8, 0.1)
+    ga = {k: v.to(DEV) for k, v in ad.items()}
+    d.inner_adamw(ga["theta"], ga["m1"], ga["m2"], ga["grad"], lr=4e-4, beta1=0.9, beta2=0.95, eps=1e-8,
+                  weight_decay=0.1, step=3)
+    torch.cuda.synchronize()
+    for k in ("theta", "m1", "m2"):
+        assert_close(W.to_f64(ga[k]), refa[k], TOL_F32, f"adamw M={M} {k}")
+    with pytest.raises(d.DilocoError) as ei:
+        d.outer_sync(torch.zeros((65536, 4), device=DEV), torch.zeros(4, device=DEV), torch.zeros(4, device=DEV),
+                     outer_lr=ETA, outer_momentum=MU)
+    assert ei.value.status == d.binding.ERR_SHAPE
+
+
 def test_eager_empty_input_is_a_noop():
     wl = wl_for(2, 8)
     g = {k: v.to(DEV) for k, v in W.outer_state(wl, 8, seed=2).items()}
