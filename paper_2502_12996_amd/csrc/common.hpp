@@ -78,7 +78,8 @@ __device__ __forceinline__ int64_t logical_block(int64_t per_xcd) {
 struct Tuning {
     int block = 0;         // threads per workgroup of the streaming kernels; 0: chosen per launch
     int xcd_remap = 0;
-    int generic_path = 0;  // eager kernel for M without a register instantiation: 0 auto, 1 LDS, 2 two-pass
+    int generic_path = 0;  // grouped eager kernel: 0 where no register instantiation exists, staging 40 replicas;
+                           // 1 for every M, staging 80; 2 for every M, staging none
     int wg_per_cu = -1;    // most workgroups of a streaming kernel resident on a CU; 0: no cap, -1: chosen per launch
 };
 Tuning& tuning();

@@ -70,7 +70,7 @@ __device__ __forceinline__ f4 sent(f4 d, const OuterScalars& sc) {
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
-constexpr int kMinStagedWaves = 2;     // LDS path only while this many wavefronts fit a CU
+constexpr int kMinStagedWaves = 2;     // replicas are staged in LDS only while this many wavefronts fit a CU
 constexpr int kTileShift = 13;  // DILOCO_STATE_TILE = 8192 elements
 constexpr int64_t kTile = (int64_t)1 << kTileShift;
 static_assert(kTile == DILOCO_STATE_TILE, "header and kernels disagree on the state tile");

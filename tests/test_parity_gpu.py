@@ -108,11 +108,12 @@ def test_eager_large_M_paths_agree_bitwise():
         assert torch.equal(a[k][..., :n], b[k][..., :n]), k
 
 
-@pytest.mark.parametrize("M", [9, 12, 16, 40, 41, 80, 83])
+@pytest.mark.parametrize("M", [2, 8, 9, 12, 16, 40, 41, 80, 83])
 def test_eager_generic_paths_agree_bitwise(M):
     """Replica counts without a register instantiation run the grouped kernel, which stages the
     first 40 (generic_path 1: 80; 2: none) replicas in LDS and reads the others twice; every
-    split promises the arithmetic of the register kernel in the same order."""
+    split promises the arithmetic of the register kernel in the same order.  A forced path also
+    replaces the register kernel (M = 2, 8), which must not change a bit either."""
     n = 20_003
     out = []
     for path in (0, 1, 2):
