@@ -92,10 +92,11 @@ def mean_over_replicas(delta):
 # --------------------------------------------------------------------------
 # Algorithm 1: standard DiLoCo, one shared set of outer parameters
 # --------------------------------------------------------------------------
-def outer_standard(theta, a, u, eta, mu, nesterov=True):
-    """theta [M, n]; a, u [n] shared by all replicas.  Returns Delta^(t)."""
+def outer_standard(theta, a, u, eta, mu, nesterov=True, comm="f32"):
+    """theta [M, n]; a, u [n] shared by all replicas.  Returns Delta^(t).  With quantised
+    communication (Section 3.2) the mean is taken over what the replicas send."""
     delta = local_outer_gradients(a, theta)          # line 7
-    delta_bar = mean_over_replicas(delta)            # lines 8-9
+    delta_bar = mean_over_replicas(sent_outer_gradients(delta, a, theta, comm))  # lines 8-9
     nesterov_step(a, u, delta_bar, eta, mu, nesterov)  # line 10
     theta[...] = a                                    # every replica restarts from the outer params
     return delta_bar

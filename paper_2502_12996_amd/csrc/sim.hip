@@ -16,9 +16,11 @@ Tuning& tuning() {
 
 bool grant_lds_for(const void* kernel, size_t lds) {
     static std::mutex lock;
-    static std::unordered_map<const void*, size_t> granted;
+    static std::unordered_map<uintptr_t, size_t> granted;  // per kernel and device
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
     std::lock_guard<std::mutex> hold(lock);
-    size_t& have = granted[kernel];
+    size_t& have = granted[reinterpret_cast<uintptr_t>(kernel) ^ ((uintptr_t)(dev + 1) << 56)];
     if (lds <= have) return true;
     if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();

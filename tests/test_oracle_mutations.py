@@ -50,6 +50,7 @@ PINS = [
     lambda: P.test_exmy_rounding_is_the_nearest_code_by_brute_force((4, 3, 16)),
     lambda: P.test_exmy_communication_stores_what_was_sent(O.outer_eager),
     lambda: P.test_exmy_communication_stores_what_was_sent(O.outer_delayed),
+    lambda: P.test_standard_outer_step_with_quantised_communication_averages_what_was_sent("bf16"),
     lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_eager),
     lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_delayed),
     S.test_checker_streaming_driver_reduces_to_the_plain_run,
@@ -183,7 +184,11 @@ def local_wrong_sign(a, theta):
     return theta - a
 
 
-def standard_no_reset(theta, a, u, eta, mu, nesterov=True):
+def standard_ignores_wire_format(theta, a, u, eta, mu, nesterov=True, comm="f32"):
+    return ORIG["outer_standard"](theta, a, u, eta, mu, nesterov)
+
+
+def standard_no_reset(theta, a, u, eta, mu, nesterov=True, comm="f32"):
     delta = O.local_outer_gradients(a, theta)
     dbar = O.mean_over_replicas(delta)
     O.nesterov_step(a, u, dbar, eta, mu, nesterov)
@@ -279,6 +284,7 @@ MUTATIONS = [
     ("outer_delayed", outer_delayed_uses_fresh_mean),
     ("mean_over_replicas", mean_forgets_division), ("mean_over_replicas", mean_wrong_divisor),
     ("local_outer_gradients", local_wrong_sign), ("outer_standard", standard_no_reset),
+    ("outer_standard", standard_ignores_wire_format),
     ("mix64", mix64_wrong_shift), ("standard_normal", normal_without_factor_two),
     ("standard_normal", normal_ignores_replica), ("round_to_bf16", bf16_truncates),
     ("is_boundary", boundary_ignores_offset),

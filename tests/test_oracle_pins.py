@@ -574,6 +574,30 @@ def test_quantised_communication_keeps_the_stale_share_identity(fn):
             np.testing.assert_allclose(G[m], (fresh[m] + others) / M, rtol=1e-10, atol=1e-16)
 
 
+@pytest.mark.parametrize("comm", ["bf16", ("exmy", 5, 10, 25)])
+def test_standard_outer_step_with_quantised_communication_averages_what_was_sent(comm):
+    """Momentum off and outer learning rate 1: the new outer parameters are the old ones minus the
+    mean of the ROUNDED outer gradients (rounded by an independent library conversion)."""
+    M, n = 4, 60
+    a0 = rnd(n, scale=0.02).astype(np.float32).astype(np.float64)
+    theta = (a0[None] - rnd(M, n, scale=1e-3)).astype(np.float32).astype(np.float64)
+    d32 = a0[None].astype(np.float32) - theta.astype(np.float32)
+    if comm == "bf16":
+        sent = torch.tensor(d32).to(torch.bfloat16).double().numpy()
+    else:
+        sent = (d32 * np.float32(1024.0)).astype(np.float16).astype(np.float64) / 1024.0
+    a, u, th = a0.copy(), np.zeros(n), theta.copy()
+    got = O.outer_standard(th, a, u, 1.0, 0.0, True, comm=comm)
+    np.testing.assert_allclose(got, sent.mean(axis=0), rtol=1e-14, atol=0)
+    np.testing.assert_allclose(a, a0 - sent.mean(axis=0), rtol=1e-14, atol=1e-18)
+    np.testing.assert_array_equal(th, np.tile(a, (M, 1)))
+    assert np.max(np.abs(sent - d32)) > 0
+    # and nothing changes without it
+    a2, u2, th2 = a0.copy(), np.zeros(n), theta.copy()
+    np.testing.assert_allclose(O.outer_standard(th2, a2, u2, 1.0, 0.0, True), (a0[None] - theta).mean(axis=0),
+                               rtol=1e-14, atol=1e-20)
+
+
 def test_full_precision_communication_is_the_default():
     M, n = 2, 9
     a0 = rnd(n)
