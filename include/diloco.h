@@ -128,6 +128,17 @@ int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, int64_t n, i
                       double outer_lr, double outer_momentum, int nesterov, void* stream);
 
 /*
+ * The same step with quantised communication (Section 3.2, "Quantized Communication"):
+ * Delta = (1/M) sum_m q(Delta_m), q the rounding to the wire format named by `comm`:
+ * 0 (none: identical to diloco_outer_sync), DILOCO_COMM_BF16 or DILOCO_COMM_EXMY(E, MN, BIAS),
+ * both defined below; anything else is DILOCO_ERR_DTYPE.
+ */
+int diloco_outer_sync_comm(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                           float* anchor, float* vel, float* mean_out,
+                           double outer_lr, double outer_momentum, int nesterov, int comm,
+                           void* stream);
+
+/*
  * Eager (Algorithm 3, lines 7-12) or naive delayed (Algorithm 2, lines 7-11) outer
  * step, fused into one read-modify-write pass.  Every replica owns its outer
  * parameters and its OuterOpt state (Section 2.2: the replicas are never

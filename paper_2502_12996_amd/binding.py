@@ -44,6 +44,8 @@ SIGNATURES = {
                                     _c_int, _c_dbl, _c_dbl, _c_dbl, _c_dbl, _c_dbl, _c_i64, _c_ptr]),
     "diloco_outer_sync": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr,
                                    _c_dbl, _c_dbl, _c_int, _c_ptr]),
+    "diloco_outer_sync_comm": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr,
+                                        _c_dbl, _c_dbl, _c_int, _c_int, _c_ptr]),
     "diloco_outer_eager": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr,
                                     _c_i64, _c_ptr, _c_dbl, _c_dbl, _c_int, _c_int, _c_int, _c_ptr]),
     "diloco_reset": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_i64, _c_ptr]),
@@ -148,13 +150,19 @@ def inner_adamw(theta, m1, m2, grad, *, n=None, lr, beta1, beta2, eps, weight_de
 
 
 def outer_sync(theta, anchor, vel, *, n=None, mean_out=None, outer_lr, outer_momentum,
-               nesterov=True, stream=None) -> None:
-    """diloco_outer_sync: theta [M, stride]; anchor, vel (and mean_out) [n] fp32."""
+               nesterov=True, comm=None, stream=None) -> None:
+    """diloco_outer_sync: theta [M, stride]; anchor, vel (and mean_out) [n] fp32.  comm (COMM_BF16 or
+    COMM_EXMY(...)) goes through diloco_outer_sync_comm."""
     M = theta.shape[0]
     n = theta.shape[1] if n is None else n
-    _check("diloco_outer_sync", lib().diloco_outer_sync(
-        _ptr(theta), _dtype_code(theta), M, n, _row_stride(theta), _ptr(anchor), _ptr(vel),
-        _ptr(mean_out), outer_lr, outer_momentum, int(nesterov), _stream(stream)))
+    if comm is None:
+        _check("diloco_outer_sync", lib().diloco_outer_sync(
+            _ptr(theta), _dtype_code(theta), M, n, _row_stride(theta), _ptr(anchor), _ptr(vel),
+            _ptr(mean_out), outer_lr, outer_momentum, int(nesterov), _stream(stream)))
+    else:
+        _check("diloco_outer_sync_comm", lib().diloco_outer_sync_comm(
+            _ptr(theta), _dtype_code(theta), M, n, _row_stride(theta), _ptr(anchor), _ptr(vel),
+            _ptr(mean_out), outer_lr, outer_momentum, int(nesterov), int(comm), _stream(stream)))
 
 
 def outer_eager(theta, anchor, vel, prev_local, prev_mean, *, n=None, outer_lr, outer_momentum,

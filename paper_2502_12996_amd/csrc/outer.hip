@@ -371,19 +371,19 @@ __global__ __launch_bounds__(64) void outer_eager_grouped_kernel(TT* __restrict_
 }
 
 // ------------------------------------------------------------------ standard DiLoCo
-// Shared outer parameters: nothing per replica has to survive the reduction, so a runtime
-// loop over m suffices.
+// Shared outer parameters: nothing per replica has to survive the reduction, so any M runs
+// through one kernel, the replicas in groups of kGroup.
 // K consecutive replicas' theta at one index: all K loads first, then the sum in replica order.
 template <int K, typename TT>
-__device__ __forceinline__ void sync_group(const TT* __restrict__ th0, int64_t stride, f4 a, double& s0, double& s1,
-                                           double& s2, double& s3) {
+__device__ __forceinline__ void sync_group(const TT* __restrict__ th0, int64_t stride, f4 a, const OuterScalars& sc,
+                                           double& s0, double& s1, double& s2, double& s3) {
     static_assert(K <= kGroup, "group too large");
     f4 th[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) th[j] = load4(th0 + j * stride);
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-        const f4 d = a - th[j];
+        const f4 d = sent(a - th[j], sc);
         s0 += (double)d.x;
         s1 += (double)d.y;
         s2 += (double)d.z;
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(kMaxBlock) void outer_sync_vec_kernel(TT* __restric
         for (int64_t i = n & ~(int64_t)3; i < n; ++i) {
             float a = load1(anchor + i), u = load1(vel + i);
             double s = 0.0;
-            for (int m = 0; m < M; ++m) s += (double)(a - load1(theta + m * stride + i));
+            for (int m = 0; m < M; ++m) s += (double)sent(a - load1(theta + m * stride + i), sc);
             float dbar = (float)(s * sc.inv_M_d);
             outer_opt(a, u, dbar, sc);
             for (int m = 0; m < M; ++m) store1(theta + m * stride + i, a);
@@ -419,15 +419,15 @@ __global__ __launch_bounds__(kMaxBlock) void outer_sync_vec_kernel(TT* __restric
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
     // replicas in groups of kGroup, a group's loads issued together; the sum runs over m = 0, 1, ...
     int m0 = 0;
-    for (; m0 + kGroup <= M; m0 += kGroup) sync_group<kGroup>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3);
+    for (; m0 + kGroup <= M; m0 += kGroup) sync_group<kGroup>(theta + m0 * stride + i, stride, a, sc, s0, s1, s2, s3);
     switch (M - m0) {
-        case 1: sync_group<1>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
-        case 2: sync_group<2>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
-        case 3: sync_group<3>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
-        case 4: sync_group<4>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
-        case 5: sync_group<5>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
-        case 6: sync_group<6>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
-        case 7: sync_group<7>(theta + m0 * stride + i, stride, a, s0, s1, s2, s3); break;
+        case 1: sync_group<1>(theta + m0 * stride + i, stride, a, sc, s0, s1, s2, s3); break;
+        case 2: sync_group<2>(theta + m0 * stride + i, stride, a, sc, s0, s1, s2, s3); break;
+        case 3: sync_group<3>(theta + m0 * stride + i, stride, a, sc, s0, s1, s2, s3); break;
+        case 4: sync_group<4>(theta + m0 * stride + i, stride, a, sc, s0, s1, s2, s3); break;
+        case 5: sync_group<5>(theta + m0 * stride + i, stride, a, sc, s0, s1, s2, s3); break;
+        case 6: sync_group<6>(theta + m0 * stride + i, stride, a, sc, s0, s1, s2, s3); break;
+        case 7: sync_group<7>(theta + m0 * stride + i, stride, a, sc, s0, s1, s2, s3); break;
         default: break;
     }
     f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
@@ -448,7 +448,7 @@ __global__ __launch_bounds__(kMaxBlock) void outer_sync_scalar_kernel(TT* theta,
     if (i >= n) return;
     float a = load1(anchor + i), u = load1(vel + i);
     double s = 0.0;
-    for (int m = 0; m < M; ++m) s += (double)(a - load1(theta + m * stride + i));
+    for (int m = 0; m < M; ++m) s += (double)sent(a - load1(theta + m * stride + i), sc);
     float dbar = (float)(s * sc.inv_M_d);
     outer_opt(a, u, dbar, sc);
     for (int m = 0; m < M; ++m) store1(theta + m * stride + i, a);
@@ -788,12 +788,14 @@ static int launch_sync(TT* theta, float* anchor, float* vel, float* mean_out, in
     return launch_status();
 }
 
-extern "C" int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
-                                 int64_t stride, float* anchor, float* vel, float* mean_out,
-                                 double outer_lr, double outer_momentum, int nesterov,
-                                 void* stream) {
+extern "C" int diloco_outer_sync_comm(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                      int64_t stride, float* anchor, float* vel, float* mean_out,
+                                      double outer_lr, double outer_momentum, int nesterov, int comm,
+                                      void* stream) {
     if (!theta || !anchor || !vel) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
+    OuterScalars wire;
+    if ((comm & 0xff) != 0 || !parse_comm(comm, wire)) return DILOCO_ERR_DTYPE;
     if (int e = check_shape(M, n, stride)) return e;
     if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
     const int es = elem_size(theta_dtype);
@@ -808,13 +810,22 @@ extern "C" int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, i
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(theta, 4 * es) && aligned_to(anchor, 16) && aligned_to(vel, 16) &&
                         aligned_to(mean_out, 16) && (M == 1 || stride % 4 == 0);
-    const OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
+    sc.comm = wire.comm, sc.q_mant = wire.q_mant, sc.q_emin = wire.q_emin, sc.q_bias = wire.q_bias, sc.q_max = wire.q_max;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)
         return launch_sync<float>(static_cast<float*>(theta), anchor, vel, mean_out, M, n, stride, sc,
                                   vec_ok, st);
     return launch_sync<__bf16>(static_cast<__bf16*>(theta), anchor, vel, mean_out, M, n, stride, sc,
                                vec_ok, st);
+}
+
+extern "C" int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                 int64_t stride, float* anchor, float* vel, float* mean_out,
+                                 double outer_lr, double outer_momentum, int nesterov,
+                                 void* stream) {
+    return diloco_outer_sync_comm(theta, theta_dtype, M, n, stride, anchor, vel, mean_out, outer_lr,
+                                  outer_momentum, nesterov, 0, stream);
 }
 
 template <typename TT, typename AV>

@@ -620,6 +620,43 @@ def test_eager_with_exmy_communication(M, variant, apply, packed, misalign, fmt)
         assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"exmy {fmt} comm {variant} {k}")
 
 
+@pytest.mark.parametrize("M", [1, 3, 8, 12])
+@pytest.mark.parametrize("comm", ["bf16", (2, 1, 11), (4, 3, 16)], ids=["bf16", "fp4", "fp8"])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_standard_outer_step_with_quantised_communication(M, comm, misalign):
+    n = 20_003
+    wl = wl_for(M, n)
+    st = W.outer_state(wl, n, seed=67, stride=n + 8)
+    theta = st["theta"][:, misalign:misalign + n]
+    a, u = st["anchor"][0, :n].clone(), st["vel"][0, :n].clone()
+    rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
+    want_mean = O.outer_standard(rt, ra, ru, ETA, MU, True, comm="bf16" if comm == "bf16" else ("exmy",) + comm)
+    gt = st["theta"].to(DEV)[:, misalign:misalign + n]
+    ga, gu, gm = a.to(DEV), u.to(DEV), torch.zeros(n, device=DEV)
+    d.outer_sync(gt, ga, gu, n=n, mean_out=gm, outer_lr=ETA, outer_momentum=MU,
+                 comm=d.COMM_BF16 if comm == "bf16" else d.COMM_EXMY(*comm))
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(gm), want_mean, TOL_F32, "mean of the rounded outer gradients")
+    assert_close(W.to_f64(ga), ra, TOL_F32, "anchor")
+    assert_close(W.to_f64(gu), ru, TOL_F32, "vel")
+    assert torch.equal(gt, ga.expand(M, n))
+    # the mean of M values of a coarse grid sits on the grid refined by 1/M: fp4 has 8 magnitudes
+    if comm != "bf16" and comm[0] + comm[1] <= 3:
+        q = 2.0 ** (1 - comm[2] - comm[1]) / M
+        r = W.to_f64(gm) / q
+        assert np.max(np.abs(r - np.rint(r))) < 1e-3
+    # comm = 0 is the plain entry point
+    p1, p2 = st["theta"].to(DEV), st["theta"].to(DEV)
+    a1, a2, u1, u2 = a.to(DEV), a.to(DEV), u.to(DEV), u.to(DEV)
+    d.outer_sync(p1, a1, u1, n=n, outer_lr=ETA, outer_momentum=MU)
+    d.outer_sync(p2, a2, u2, n=n, outer_lr=ETA, outer_momentum=MU, comm=0)
+    torch.cuda.synchronize()
+    assert torch.equal(a1, a2) and torch.equal(u1, u2) and torch.equal(p1, p2)
+    with pytest.raises(d.DilocoError) as ei:
+        d.outer_sync(p1, a1, u1, n=n, outer_lr=ETA, outer_momentum=MU, comm=1)
+    assert ei.value.status == d.binding.ERR_DTYPE
+
+
 @pytest.mark.parametrize("bits", [0x200, 0x400, 0x800, 1 << 28, 0x100 | 0x200 | (4 << 12) | (3 << 16),
                                   "E0M3b0", "E9M1b0", "E5M11b0", "E8M7b127", "E8M2b100", "E4M3b-120", "E4M3b125", "E2M10b118", "E4M3b-113"])
 def test_unknown_variant_bits_are_rejected(bits):
