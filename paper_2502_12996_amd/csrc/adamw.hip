@@ -19,12 +19,17 @@ struct AdamScalars {
 // m1 <- b1 m1 + (1-b1) g ; m2 <- b2 m2 + (1-b2) g^2 ;
 // theta <- theta - lr ( m1_hat / (sqrt(m2_hat) + eps) + wd theta )
 template <typename T>
-__device__ __forceinline__ void adamw_update(T& th, T& m1, T& m2, T g, const AdamScalars& sc) {
+__device__ __forceinline__ void adamw_update(T& th, T& m1, T& m2, T g, const AdamScalars& sc, float inv_bc1,
+                                             float inv_bc2) {
     m1 = fma_(splat<T>(sc.beta1), m1, sc.omb1 * g);
     m2 = fma_(splat<T>(sc.beta2), m2, (sc.omb2 * g) * g);
-    const T denom = sqrt_(m2 * sc.inv_bc2) + sc.eps;
-    const T upd = (m1 * sc.inv_bc1) / denom;
+    const T denom = sqrt_(m2 * inv_bc2) + sc.eps;
+    const T upd = (m1 * inv_bc1) / denom;
     th = fma_(splat<T>(-sc.lr), fma_(splat<T>(sc.wd), th, upd), th);
+}
+template <typename T>
+__device__ __forceinline__ void adamw_update(T& th, T& m1, T& m2, T g, const AdamScalars& sc) {
+    adamw_update(th, m1, m2, g, sc, sc.inv_bc1, sc.inv_bc2);
 }
 
 template <typename PT, typename GT>
@@ -165,11 +170,8 @@ __global__ __launch_bounds__(kMaxBlock) void quadratic_phase_kernel(
                 const uint64_t key = mix64(k0 + kGolden * (uint64_t)(m + 1));
                 float z0, z1;
                 normal_pair(key, gi >> 1, z0, z1);
-                AdamScalars st = sc;
-                st.inv_bc1 = ps.inv_bc1[s];
-                st.inv_bc2 = ps.inv_bc2[s];
                 const float g = fmaf(noise_std, (gi & 1) ? z1 : z0, hh * (t - ss));
-                adamw_update(t, a, b, g, st);
+                adamw_update(t, a, b, g, sc, ps.inv_bc1[s], ps.inv_bc2[s]);
             }
             theta[i] = t;
             m1[i] = a;
@@ -190,11 +192,8 @@ __global__ __launch_bounds__(kMaxBlock) void quadratic_phase_kernel(
         normal_pair(key, j, z0, z1);
         normal_pair(key, j + 1, z2, z3);
         const f4 z = {z0, z1, z2, z3};
-        AdamScalars st = sc;
-        st.inv_bc1 = ps.inv_bc1[s];
-        st.inv_bc2 = ps.inv_bc2[s];
         const f4 g = fma_(splat<f4>(noise_std), z, hh * (t - ss));
-        adamw_update(t, a, b, g, st);
+        adamw_update(t, a, b, g, sc, ps.inv_bc1[s], ps.inv_bc2[s]);
     }
     store4(theta + i, t);
     store4(m1 + i, a);
