@@ -94,7 +94,8 @@ constexpr int kLdsPerCu = 160 * 1024;  // gfx950
 // only `cap` workgroups fit a CU's 160 KB.  Left to itself (block 0, wg_per_cu -1) a launch uses
 // one-wavefront workgroups and as many of them per CU as bring `target_bytes` of loads in flight,
 // given that a wavefront issues `wave_load_bytes` before its first store (at least 2; from 4 up a
-// multiple of 4, one SIMD's share each; no throttle from 32 up).  An explicit block size switches the throttle off unless wg_per_cu is set too.
+// multiple of 4, one SIMD's share each; no throttle from 32 up).  An explicit block size
+// switches the throttle off unless wg_per_cu is set too.
 struct Shape {
     int block;
     size_t lds;
@@ -127,8 +128,8 @@ inline Shape launch_shape(int64_t wave_load_bytes, int64_t target_bytes) {
 // Workgroup size of the kernels that take no throttle.
 inline int plain_block() { return tuning().block ? tuning().block : 256; }
 // More than 48 KB of dynamic LDS has to be granted per kernel, once: the largest size granted so
-// far is remembered per kernel, so that a launch in steady state makes no runtime call besides
-// the launch itself.  false if the runtime refuses.
+// far is remembered per kernel and device, so that a launch in steady state sets no attribute.
+// false if the runtime refuses.
 bool grant_lds_for(const void* kernel, size_t lds);
 template <typename K>
 inline bool grant_lds(K kernel, size_t lds) {
