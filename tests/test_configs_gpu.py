@@ -228,6 +228,85 @@ def test_full_size_inner_adamw_per_call(name):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("name", ["t150m", "t550m", "t2b4_bf16"])
+def test_full_size_standard_outer_step_per_call(name):
+    """Algorithm 1's outer step at the configurations' full sizes, shared outer parameters."""
+    wl = W.WORKLOADS[name]
+    M, n = wl.M, wl.n
+    bf16 = wl.theta_dtype == "bf16"
+    st = W.outer_state(wl, n, device=DEV)
+    theta = st["theta"]
+    a, u = st["anchor"][0].clone(), st["vel"][0].clone()
+    mean = torch.empty(n, device=DEV)
+    del st
+    torch.cuda.empty_cache()
+    chunks = big_chunks(n)
+    ref = [(f64(theta[:, lo:hi]), f64(a[lo:hi]), f64(u[lo:hi])) for (lo, hi) in chunks]
+    d.outer_sync(theta, a, u, mean_out=mean, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for (rt, ra, ru), (lo, hi) in zip(ref, chunks):
+        dbar = O.outer_standard(rt, ra, ru, wl.outer_lr, wl.outer_momentum, True)
+        worst = max(worst, assert_close(f64(a[lo:hi]), ra, TOL_F32, f"{name} anchor [{lo},{hi})") / TOL_F32)
+        worst = max(worst, assert_close(f64(u[lo:hi]), ru, TOL_F32, f"{name} vel [{lo},{hi})") / TOL_F32)
+        worst = max(worst, assert_close(f64(mean[lo:hi]), dbar, TOL_F32, f"{name} mean [{lo},{hi})") / TOL_F32)
+    # at any size: every replica restarts from the new outer parameters
+    for m in range(M):
+        assert torch.equal(theta[m], a.to(theta.dtype))
+    print(f"{name}: worst standard outer step error / tolerance {worst:.3f}")
+    del theta, a, u, mean
+    torch.cuda.empty_cache()
+
+
+def test_t550m_packed_eager_step_with_fp4_communication():
+    """Config 3 with float4 (E2M1) outer gradients on the wire: the recorded codes bit for bit."""
+    wl = W.WORKLOADS["t550m"]
+    M, n = wl.M, wl.n
+    fmt = (2, 1, 11)
+    st = W.outer_state(wl, n, device=DEV)
+    chunks = big_chunks(n)
+    ref = [{k: f64(v[..., lo:hi]) for k, v in st.items()} for (lo, hi) in chunks]
+    state = torch.empty(d.packed_state_elems(M, n), device=DEV)
+    d.pack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
+                 prev_mean=st["prev_mean"])
+    d.outer_eager_packed(st["theta"], state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum,
+                         variant=d.EAGER | d.COMM_EXMY(*fmt))
+    d.unpack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
+                   prev_mean=st["prev_mean"])
+    torch.cuda.synchronize()
+    for r, (lo, hi) in zip(ref, chunks):
+        O.outer_eager(r["theta"], r["anchor"], r["vel"], r["prev_local"], r["prev_mean"],
+                      wl.outer_lr, wl.outer_momentum, True, True, comm=("exmy",) + fmt)
+        assert np.array_equal(f64(st["prev_local"][:, lo:hi]), r["prev_local"])
+        for k in r:
+            assert_close(f64(st[k][..., lo:hi]), r[k], TOL_F32, f"fp4 comm {k} [{lo},{hi})")
+    # at any size: at most 15 distinct sent values
+    assert torch.unique(st["prev_local"][0, : 1 << 24]).numel() <= 15
+    del st, state
+    torch.cuda.empty_cache()
+
+
+def test_quadratic_fused_phase_at_full_size_is_bit_identical():
+    """Config 5's shape: one fused pass over a whole phase (H = 50) against 50 separate steps."""
+    wl = W.WORKLOADS["quadratic"]
+    M, n, H = wl.M, wl.n, wl.H
+    h = W.log_uniform((n,), 1e-3, 1.0, tag="h", device=DEV)
+    star = W.normal((n,), 1.0, tag="theta_star", device=DEV)
+    kw = dict(noise_std=wl.noise_std, seed=W.BASE_SEED, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
+              weight_decay=wl.weight_decay)
+    a = [torch.zeros((M, n), device=DEV) for _ in range(3)]
+    b = [torch.zeros((M, n), device=DEV) for _ in range(3)]
+    for first in (1, H + 1):
+        for t in range(first, first + H):
+            d.sim_quadratic_inner(*a, h, star, step=t, **kw)
+        d.sim_quadratic_phase(*b, h, star, step_first=first, steps=H, **kw)
+        torch.cuda.synchronize()
+        for x, y, name in zip(a, b, ("theta", "m1", "m2")):
+            assert torch.equal(x, y), (name, first)
+    del a, b, h, star
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ config 5: noisy quadratic
 QUAD_WINDOWS = [(0, 4096), ((1 << 25) + 4096, (1 << 25) + 8192)]
 # 2000 AdamW steps and 40 outer steps with fp32 state against float64 state, the noise drawn
