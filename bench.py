@@ -298,6 +298,24 @@ def main():
         copy_ms = t if copy_ms is None else min(copy_ms, t)
     set_shape(shape_default)
     copy_gbps = 8 * n / (copy_ms * 1e-3) / 1e9
+    del cbuf, src, dst
+
+    # ceiling for the eager step's own access pattern: a bare in-place read-modify-write over
+    # K = 4M + 1 separated rows (no arithmetic), in its best launch shape
+    K = 4 * M + 1
+    rmw_gbps, shape_rmw = None, None
+    if K in (5, 9, 17, 33):
+        nr = min(n & ~3, 1 << 28)
+        rbuf = torch.empty((K, nr), dtype=torch.float32, device=dev).normal_(0, 1e-3)
+        for sh in [(0, x, -1) for x in (0, 1)] + [(64, x, c) for x in (0, 1) for c in (2, 3, 4, 6, 8)]:
+            set_shape(sh)
+            d.sim_stream_rmw(rbuf)
+            t = timed(lambda: d.sim_stream_rmw(rbuf), 5)[2]
+            g = 8 * K * nr / (t * 1e-3) / 1e9
+            if rmw_gbps is None or g > rmw_gbps:
+                rmw_gbps, shape_rmw = g, sh
+        set_shape(shape_default)
+        del rbuf
 
     outer_bytes, inner_bytes = algorithmic_bytes(wl, n)
     outer_gbps = outer_bytes / (outer_ms * 1e-3) / 1e9
@@ -325,13 +343,16 @@ def main():
                        "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS},
         **extra,
         "copy_ceiling_GBps": copy_gbps,
+        "stream_rmw_ceiling": None if rmw_gbps is None else {"K": K, "GBps": rmw_gbps,
+                                                             "launch": shape_json(shape_rmw)},
         "roofline": {"bound": "hbm", "kernel": "outer_eager_reg_kernel<%d, %s, eager, %s>" % (
                          M, "bf16" if bf16 else "float", "TiledState" if packed else "RowState"), "achieved": outer_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": outer_gbps / HBM_PEAK_GBPS,
                      "frac_of_copy": outer_gbps / copy_gbps,
+                     "frac_of_stream_rmw": None if rmw_gbps is None else outer_gbps / rmw_gbps,
                      "traffic": stored_traffic(wl.name, args.layout)},
     }
-    del st, ad, theta, m1, m2, grad, src, dst, cbuf
+    del st, ad, theta, m1, m2, grad
     if packed:
         del state
     torch.cuda.empty_cache()

@@ -76,6 +76,16 @@ int diloco_sim_quadratic_loss(const float* theta, int M, int64_t n, int64_t stri
 int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream);
 
 /*
+ * In-place sweep over K rows of n floats, `stride` floats apart: each 16-byte piece of every
+ * row is read and written back unchanged, with the access shape of the outer steps (a lane
+ * touches all K rows at one index).  No arithmetic: the rate it reaches is what the memory
+ * system gives a read-modify-write over K separated streams, the ceiling the eager outer
+ * step (K = 4M + 1) is compared with.  K in {1, 2, 4, 5, 8, 9, 16, 17, 33}; n a multiple of 4;
+ * base 16-byte aligned, stride a multiple of 4.
+ */
+int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stride, void* stream);
+
+/*
  * Launch tuning for measurements.  Keys:
  *   "block"        threads per workgroup of the streaming kernels: 64..512, power of two; 0 (the
  *                  default) lets each launch choose: one-wavefront workgroups, throttled as below.

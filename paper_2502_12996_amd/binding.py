@@ -64,6 +64,7 @@ SIGNATURES = {
     "diloco_sim_quadratic_phase": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_int, _c_i64, _c_i64, _c_ptr,
                                             _c_ptr, _c_dbl, ctypes.c_uint64, _c_i64, _c_dbl, _c_dbl,
                                             _c_dbl, _c_dbl, _c_dbl, _c_i64, _c_int, _c_ptr]),
+    "diloco_sim_stream_rmw": (_c_int, [_c_ptr, _c_int, _c_i64, _c_i64, _c_ptr]),
     "diloco_sim_loss_workspace": (_c_i64, [_c_i64]),
     "diloco_sim_quadratic_loss": (_c_int, [_c_ptr, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr,
                                            _c_i64, _c_ptr, _c_ptr]),
@@ -303,6 +304,14 @@ def sim_quadratic_loss(theta, h, theta_star, partials, loss_out, *, n=None, stre
 def sim_stream_copy(dst, src, *, stream=None) -> None:
     _check("diloco_sim_stream_copy", lib().diloco_sim_stream_copy(
         _ptr(dst), _ptr(src), src.numel(), _stream(stream)))
+
+
+def sim_stream_rmw(rows, *, n=None, stream=None) -> None:
+    """rows [K, stride] fp32: every row's first n elements read and written back in place."""
+    K = rows.shape[0]
+    n = rows.shape[1] if n is None else n
+    _check("diloco_sim_stream_rmw", lib().diloco_sim_stream_rmw(_ptr(rows), K, n, _row_stride(rows),
+                                                                _stream(stream)))
 
 
 def tune(key: str, value: int) -> None:

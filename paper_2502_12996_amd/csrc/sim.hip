@@ -85,6 +85,33 @@ __global__ __launch_bounds__(kMaxBlock) void stream_copy_kernel(float* __restric
     store4(dst + (v << 2), load4(src + (v << 2)));
 }
 
+// In-place sweep over K rows `stride` apart: every lane loads its 16 bytes of all K rows, then
+// stores them back unchanged.  No arithmetic: what is left is the memory system's rate for a
+// read-modify-write over K separated streams, the access pattern of the outer steps.
+template <int K>
+__global__ __launch_bounds__(kMaxBlock) void stream_rmw_kernel(float* __restrict__ base, int64_t stride,
+                                                               int64_t n, int64_t per_xcd) {
+    const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
+    if (v >= (n >> 2)) return;
+    f4 x[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) x[k] = load4(base + k * stride + (v << 2));
+#pragma unroll
+    for (int k = 0; k < K; ++k) store4(base + k * stride + (v << 2), x[k]);
+}
+
+template <int K>
+static int launch_rmw(float* base, int64_t stride, int64_t n, hipStream_t st) {
+    const Shape shape = launch_shape((int64_t)64 * 16 * K, kInFlightTarget);
+    const int64_t threads = n >> 2;
+    if (!grid_fits(threads, shape.block)) return DILOCO_ERR_SHAPE;
+    Grid g = make_grid(threads, shape.block);
+    if (!grant_lds(&stream_rmw_kernel<K>, shape.lds)) return DILOCO_ERR_LAUNCH;
+    hipLaunchKernelGGL((stream_rmw_kernel<K>), dim3(g.blocks), dim3(shape.block), shape.lds, st, base, stride, n,
+                       g.per_xcd);
+    return launch_status();
+}
+
 static int64_t loss_blocks(int64_t n) {
     int64_t b = (n + kLossBlock * 4 - 1) / (kLossBlock * 4);
     if (b < 1) b = 1;
@@ -139,6 +166,27 @@ extern "C" int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, v
     hipLaunchKernelGGL(stream_copy_kernel, dim3(g.blocks), dim3(block), shape.lds,
                        static_cast<hipStream_t>(stream), dst, src, n, g.per_xcd);
     return launch_status();
+}
+
+extern "C" int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stride, void* stream) {
+    if (!base) return DILOCO_ERR_NULL;
+    if (n < 0 || (n & 3) || stride < n || K < 1) return DILOCO_ERR_SHAPE;
+    if (stride > ((int64_t)1 << 50) / K) return DILOCO_ERR_SHAPE;
+    if (!aligned_to(base, 16) || (K > 1 && stride % 4 != 0)) return DILOCO_ERR_ALIGN;
+    if (n == 0) return DILOCO_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (K) {
+        case 1: return launch_rmw<1>(base, stride, n, st);
+        case 2: return launch_rmw<2>(base, stride, n, st);
+        case 4: return launch_rmw<4>(base, stride, n, st);
+        case 5: return launch_rmw<5>(base, stride, n, st);
+        case 8: return launch_rmw<8>(base, stride, n, st);
+        case 9: return launch_rmw<9>(base, stride, n, st);
+        case 16: return launch_rmw<16>(base, stride, n, st);
+        case 17: return launch_rmw<17>(base, stride, n, st);
+        case 33: return launch_rmw<33>(base, stride, n, st);
+        default: return DILOCO_ERR_SHAPE;
+    }
 }
 
 // ---------------------------------------------------------------- streaming schedule (host only)

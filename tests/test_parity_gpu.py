@@ -194,6 +194,25 @@ def test_very_many_replicas(M, n):
     assert ei.value.status == d.binding.ERR_SHAPE
 
 
+@pytest.mark.parametrize("K", [1, 2, 4, 5, 8, 9, 16, 17, 33])
+def test_stream_rmw_leaves_the_rows_as_they_are(K):
+    n = 70_004
+    rows = torch.empty((K, n + 8), device=DEV).normal_()
+    before = rows.clone()
+    d.sim_stream_rmw(rows, n=n)
+    d.tune("wg_per_cu", 2)
+    d.sim_stream_rmw(rows, n=n)
+    d.tune("wg_per_cu", -1)
+    torch.cuda.synchronize()
+    assert torch.equal(rows, before)
+    for bad in (dict(n=n + 1), dict(n=n + 12)):
+        with pytest.raises(d.DilocoError):
+            d.sim_stream_rmw(rows, **bad)
+    if K == 4:
+        with pytest.raises(d.DilocoError):
+            d.sim_stream_rmw(torch.zeros((3, 64), device=DEV))
+
+
 def test_eager_empty_input_is_a_noop():
     wl = wl_for(2, 8)
     g = {k: v.to(DEV) for k, v in W.outer_state(wl, 8, seed=2).items()}
