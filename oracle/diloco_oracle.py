@@ -1,9 +1,9 @@
 """CPU checker for the DiLoCo optimizer sweep.  TEST INFRASTRUCTURE ONLY.
 
 A plain, slow, single-threaded float64 NumPy statement of what the hot path
-computes: the inner AdamW step (line 5 of Algorithms 1-3), the standard outer
-step (Algorithm 1, lines 7-10), the naive delayed outer step (Algorithm 2,
-lines 7-11) and the eager outer step (Algorithm 3, lines 7-12), plus the noisy
+computes: the inner AdamW step (InnerOpt of Algorithms 1-3), the standard outer
+step (Algorithm 1), the naive delayed outer step (Algorithm 2) and the eager
+outer step (Algorithm 3), plus the noisy
 quadratic used as a stand-in training problem.  It shares no code with the HIP
 library and is imported only by the tests, by the smoke check and by the
 benchmark's cpu_baseline leg.  Nothing in the product path may call it.
@@ -46,7 +46,7 @@ U64 = np.uint64
 
 
 # --------------------------------------------------------------------------
-# InnerOpt: AdamW (Algorithms 1-3, line 5)
+# InnerOpt: AdamW (the inner optimization step of Algorithms 1-3)
 # --------------------------------------------------------------------------
 def adamw_step(theta, m1, m2, g, t, lr, beta1, beta2, eps, weight_decay):
     """One AdamW step, t >= 1 is the global step count (never reset).
@@ -64,7 +64,7 @@ def adamw_step(theta, m1, m2, g, t, lr, beta1, beta2, eps, weight_decay):
 
 
 # --------------------------------------------------------------------------
-# OuterOpt: SGD with (Nesterov) momentum (Algorithm 1 line 10, 2 line 11, 3 line 12)
+# OuterOpt: SGD with (Nesterov) momentum (the outer optimization step of Algorithms 1-3)
 # --------------------------------------------------------------------------
 def nesterov_step(a, u, G, eta, mu, nesterov=True):
     """u <- mu u + G ; a <- a - eta (G + mu u) (Nesterov) or a <- a - eta u (heavy ball)."""
@@ -76,12 +76,12 @@ def nesterov_step(a, u, G, eta, mu, nesterov=True):
 
 
 def local_outer_gradients(a, theta):
-    """Line 7: Delta_m = theta_m^(t-H) - theta_m^(t).  `a` is [n] (shared) or [M, n]."""
+    """Local outer gradient: Delta_m = theta_m^(t-H) - theta_m^(t).  `a` is [n] (shared) or [M, n]."""
     return a - theta  # broadcasting covers the shared anchor
 
 
 def mean_over_replicas(delta):
-    """Line 8: Delta = (1/M) sum_m Delta_m, summed left to right in m."""
+    """The all-reduce: Delta = (1/M) sum_m Delta_m, summed left to right in m."""
     M = delta.shape[0]
     s = delta[0].copy()
     for m in range(1, M):
@@ -95,9 +95,9 @@ def mean_over_replicas(delta):
 def outer_standard(theta, a, u, eta, mu, nesterov=True, comm="f32"):
     """theta [M, n]; a, u [n] shared by all replicas.  Returns Delta^(t).  With quantised
     communication (Section 3.2) the mean is taken over what the replicas send."""
-    delta = local_outer_gradients(a, theta)          # line 7
-    delta_bar = mean_over_replicas(sent_outer_gradients(delta, a, theta, comm))  # lines 8-9
-    nesterov_step(a, u, delta_bar, eta, mu, nesterov)  # line 10
+    delta = local_outer_gradients(a, theta)          # local outer gradients
+    delta_bar = mean_over_replicas(sent_outer_gradients(delta, a, theta, comm))  # blocking all-reduce
+    nesterov_step(a, u, delta_bar, eta, mu, nesterov)  # outer optimization on the shared parameters
     theta[...] = a                                    # every replica restarts from the outer params
     return delta_bar
 
@@ -166,12 +166,12 @@ def outer_delayed(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True, 
     """theta, a, u, P [M, n]; D [n].  apply_update=False is the t = H boundary,
     where the listing applies no outer step: the replica just continues from its
     own parameters, which become its next anchor."""
-    delta = local_outer_gradients(a, theta)          # line 7
+    delta = local_outer_gradients(a, theta)          # local outer gradients
     wire = sent_outer_gradients(delta, a, theta, comm)
-    delta_bar = mean_over_replicas(wire)             # line 8 (arrives one phase later)
-    if apply_update:                                 # line 9: t > H
+    delta_bar = mean_over_replicas(wire)             # async all-reduce (arrives one phase later)
+    if apply_update:                                 # t > H
         for m in range(theta.shape[0]):
-            nesterov_step(a[m], u[m], D, eta, mu, nesterov)   # lines 10-11 with Delta^(t-H)
+            nesterov_step(a[m], u[m], D, eta, mu, nesterov)   # outer step with the received Delta^(t-H)
     else:
         a[...] = theta
     theta[...] = a
@@ -183,7 +183,8 @@ def outer_delayed(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True, 
 # Algorithm 3: eager updates with delayed outer gradients
 # --------------------------------------------------------------------------
 def eager_combination(delta, P, D):
-    """Line 11: Delta~_m = (1/M)(Delta_m^(t) - Delta_m^(t-H)) + Delta^(t-H)."""
+    """Algorithm 3's mix of fresh local and stale averaged outer gradients:
+    Delta~_m = (1/M)(Delta_m^(t) - Delta_m^(t-H)) + Delta^(t-H)."""
     M = delta.shape[0]
     return (delta - P) / M + D
 
@@ -191,15 +192,15 @@ def eager_combination(delta, P, D):
 def outer_eager(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True, comm="f32"):
     """theta, a, u, P [M, n]; D [n].  All Delta~_m are formed from the old P and D
     before either is overwritten.  With quantised communication P holds what the replica
-    sent, so that line 11 removes exactly its own stale share of D, and the fresh local
+    sent, so that the eager combination removes exactly its own stale share of D, and the fresh local
     Delta_m enters unrounded (the replica has it in full precision)."""
-    delta = local_outer_gradients(a, theta)          # line 7
+    delta = local_outer_gradients(a, theta)          # local outer gradients
     wire = sent_outer_gradients(delta, a, theta, comm)
-    delta_bar = mean_over_replicas(wire)             # line 8
-    if apply_update:                                 # line 9: t > H
-        G = eager_combination(delta, P, D)           # lines 10-11
+    delta_bar = mean_over_replicas(wire)             # async all-reduce
+    if apply_update:                                 # t > H
+        G = eager_combination(delta, P, D)           # receive Delta^(t-H), combine
         for m in range(theta.shape[0]):
-            nesterov_step(a[m], u[m], G[m], eta, mu, nesterov)  # line 12
+            nesterov_step(a[m], u[m], G[m], eta, mu, nesterov)  # outer optimization per replica
     else:
         a[...] = theta
     theta[...] = a

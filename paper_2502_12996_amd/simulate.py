@@ -9,7 +9,7 @@ lives here; every arithmetic step runs in the library's kernels:
     lines 7-12  diloco_outer_sync / diloco_outer_eager / diloco_outer_eager_packed
     loss        diloco_sim_quadratic_loss    (at the replica mean of the outer parameters)
 
-    python -m paper_2502_12996_amd.simulate            # BASELINE configuration 5: 64M params,
+    python -m paper_2502_12996_amd.simulate            # benchmark configuration 5: 64M params,
                                                        # M=4, H=50, 40 phases, four variants
 """
 from __future__ import annotations
