@@ -193,19 +193,22 @@ def outer_eager(theta, a, u, P, D, eta, mu, nesterov=True, apply_update=True, co
     """theta, a, u, P [M, n]; D [n].  All Delta~_m are formed from the old P and D
     before either is overwritten.  With quantised communication P holds what the replica
     sent, so that the eager combination removes exactly its own stale share of D, and the fresh local
-    Delta_m enters unrounded (the replica has it in full precision)."""
+    Delta_m enters unrounded (the replica has it in full precision).
+    D = None: the previous mean is not kept at all.  When all replicas are at hand it is, by its
+    definition, the mean of the previous local outer gradients P, and is formed from them."""
     delta = local_outer_gradients(a, theta)          # local outer gradients
     wire = sent_outer_gradients(delta, a, theta, comm)
     delta_bar = mean_over_replicas(wire)             # async all-reduce
     if apply_update:                                 # t > H
-        G = eager_combination(delta, P, D)           # receive Delta^(t-H), combine
+        G = eager_combination(delta, P, mean_over_replicas(P) if D is None else D)  # receive Delta^(t-H), combine
         for m in range(theta.shape[0]):
             nesterov_step(a[m], u[m], G[m], eta, mu, nesterov)  # outer optimization per replica
     else:
         a[...] = theta
     theta[...] = a
     P[...] = wire
-    D[...] = delta_bar
+    if D is not None:
+        D[...] = delta_bar
 
 
 def reset(theta, a):

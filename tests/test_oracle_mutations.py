@@ -51,6 +51,8 @@ PINS = [
     lambda: P.test_exmy_communication_stores_what_was_sent(O.outer_eager),
     lambda: P.test_exmy_communication_stores_what_was_sent(O.outer_delayed),
     lambda: P.test_standard_outer_step_with_quantised_communication_averages_what_was_sent("bf16"),
+    lambda: P.test_previous_mean_is_the_mean_of_the_previous_locals_so_it_need_not_be_kept("f32"),
+    lambda: P.test_previous_mean_is_the_mean_of_the_previous_locals_so_it_need_not_be_kept("bf16"),
     lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_eager),
     lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_delayed),
     S.test_checker_streaming_driver_reduces_to_the_plain_run,
@@ -137,6 +139,22 @@ def outer_eager_rotates_first(theta, a, u, Pp, D, eta, mu, nesterov=True, apply_
     else:
         a[...] = theta
     theta[...] = a
+
+
+def outer_eager_forms_the_mean_from_the_fresh_locals(theta, a, u, Pp, D, eta, mu, nesterov=True, apply_update=True,
+                                                     comm="f32"):
+    if D is not None:
+        return ORIG["outer_eager"](theta, a, u, Pp, D, eta, mu, nesterov, apply_update, comm)
+    delta = O.local_outer_gradients(a, theta)
+    wire = O.sent_outer_gradients(delta, a, theta, comm)
+    if apply_update:
+        G = O.eager_combination(delta, Pp, O.mean_over_replicas(wire))
+        for m in range(theta.shape[0]):
+            O.nesterov_step(a[m], u[m], G[m], eta, mu, nesterov)
+    else:
+        a[...] = theta
+    theta[...] = a
+    Pp[...] = wire
 
 
 def outer_eager_always_applies(theta, a, u, Pp, D, eta, mu, nesterov=True, apply_update=True, comm="f32"):
@@ -281,6 +299,7 @@ MUTATIONS = [
     ("eager_combination", eager_drops_mean),
     ("outer_eager", outer_eager_rotates_first), ("outer_eager", outer_eager_always_applies),
     ("outer_eager", outer_eager_rounds_local_too),
+    ("outer_eager", outer_eager_forms_the_mean_from_the_fresh_locals),
     ("outer_delayed", outer_delayed_uses_fresh_mean),
     ("mean_over_replicas", mean_forgets_division), ("mean_over_replicas", mean_wrong_divisor),
     ("local_outer_gradients", local_wrong_sign), ("outer_standard", standard_no_reset),

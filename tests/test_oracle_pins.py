@@ -598,6 +598,35 @@ def test_standard_outer_step_with_quantised_communication_averages_what_was_sent
                                rtol=1e-14, atol=1e-20)
 
 
+@pytest.mark.parametrize("comm", ["f32", "bf16"])
+def test_previous_mean_is_the_mean_of_the_previous_locals_so_it_need_not_be_kept(comm):
+    """After every eager boundary the stored mean equals the mean of the stored local outer
+    gradients (it is their all-reduce), so a run that never stores it and forms it from them
+    walks the same trajectory; checked against the run that stores it, and by hand for one phase."""
+    M, n, phases = 3, 40, 6
+    rng = np.random.default_rng(21)
+    a0 = rng.standard_normal(n) * 0.02
+    keep = dict(theta=np.tile(a0, (M, 1)), a=np.tile(a0, (M, 1)), u=np.zeros((M, n)), P=np.zeros((M, n)),
+                D=np.zeros(n))
+    drop = {k: v.copy() for k, v in keep.items() if k != "D"}
+    for k in range(phases):
+        step = rng.standard_normal((M, n)) * 1e-3
+        for s in (keep, drop):
+            s["theta"] = (s["theta"] + step).astype(np.float32).astype(np.float64)
+        O.outer_eager(keep["theta"], keep["a"], keep["u"], keep["P"], keep["D"], 0.7, 0.9, True, k > 0, comm=comm)
+        O.outer_eager(drop["theta"], drop["a"], drop["u"], drop["P"], None, 0.7, 0.9, True, k > 0, comm=comm)
+        np.testing.assert_array_equal(keep["D"], keep["P"].sum(axis=0) / M)
+        for name in drop:
+            np.testing.assert_array_equal(keep[name], drop[name], err_msg=f"{name} after phase {k}")
+    # one phase by hand, with a previous mean that only exists as the mean of P
+    P = rng.standard_normal((M, n)) * 1e-3
+    a = np.tile(a0, (M, 1)); theta = a - rng.standard_normal((M, n)) * 1e-3; u = np.zeros((M, n))
+    delta = a - theta
+    want_G = (delta - P) / M + P.mean(axis=0)
+    O.outer_eager(theta, a, u, P.copy(), None, 1.0, 0.0, True, True)
+    np.testing.assert_allclose(a, a0[None] - want_G, rtol=1e-12, atol=1e-18)
+
+
 def test_full_precision_communication_is_the_default():
     M, n = 2, 9
     a0 = rnd(n)
