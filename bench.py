@@ -250,6 +250,21 @@ def main():
         q4ms = timed(run_q4, 5)[2]
         extra["outer_step_fp4_comm"] = {"ms": q4ms, "GBps": outer_bytes_fn(wl, n) / (q4ms * 1e-3) / 1e9}
 
+    if packed and M <= 8:
+        # the previous mean formed from the previous local outer gradients instead of kept: one
+        # stream of 4M+1 less each way, priced at its own bytes
+        set_shape(shape_outer)
+        es_ = 2 if bf16 else 4
+        lean_bytes = 2 * (M * es_ + 12 * M) * n
+
+        def run_lean():
+            d.outer_eager_packed(theta, state, n=n, variant=d.EAGER | d.STATE_NO_MEAN, **okw)
+        run_lean()
+        lms = timed(run_lean, 7)[3]
+        extra["outer_step_no_stored_mean"] = {"ms": lms, "bytes_per_index": lean_bytes // n,
+                                              "GBps": lean_bytes / (lms * 1e-3) / 1e9,
+                                              "params_per_s": n / (lms * 1e-3)}
+
     # the standard (Algorithm 1) outer step on the same replicas: shared outer parameters
     es = 2 if bf16 else 4
     sa = W.normal((n,), wl.std_anchor, tag="anchor", device=dev)

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libdiloco.so")
 F32, BF16 = 0, 1
 EAGER, DELAYED = 0, 1
 COMM_BF16 = 0x100   # OR into `variant`: outer gradients cross the wire in bf16
+STATE_NO_MEAN = 0x400   # OR into an EAGER `variant`: the previous mean is formed from prev_local, not kept
 
 
 def COMM_EXMY(E: int, Mn: int, bias: int) -> int:

@@ -30,6 +30,7 @@ struct OuterScalars {
     int q_mant;      // ExMy: mantissa bits
     int q_emin;      // ExMy: exponent of the spacing of the subnormals, 1 - bias - mantissa bits
     int q_bias;      // ExMy: exponent bias
+    int no_mean;     // eager only: the previous mean is not kept; it is formed from the previous locals
     float q_max;     // ExMy: largest value of the format
 };
 enum { COMM_F32 = 0, COMM_BF16 = 1, COMM_EXMY = 2 };
@@ -70,6 +71,7 @@ __device__ __forceinline__ f4 sent(f4 d, const OuterScalars& sc) {
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
+constexpr int kMaxRegisterReplicas = 8;  // register-resident eager kernels exist for M = 1..8
 constexpr int kMinStagedWaves = 2;     // replicas are staged in LDS only while this many wavefronts fit a CU
 constexpr int kTileShift = 13;  // DILOCO_STATE_TILE = 8192 elements
 constexpr int64_t kTile = (int64_t)1 << kTileShift;
@@ -125,7 +127,14 @@ __device__ void eager_element(TT* theta, SV sv, int M, int64_t stride, int64_t i
         s += (double)sent(a - th, sc);
     }
     const float dbar = (float)(s * sc.inv_M_d);
-    const float Dold = (MODE == MODE_RECORD) ? 0.f : load1(sv.d(i));
+    float Dold = 0.f;
+    if (MODE == MODE_EAGER && sc.no_mean) {
+        double t = 0.0;
+        for (int m = 0; m < M; ++m) t += (double)load1(sv.p(m, i));
+        Dold = (float)(t * sc.inv_M_d);
+    } else if (MODE != MODE_RECORD) {
+        Dold = load1(sv.d(i));
+    }
     for (int m = 0; m < M; ++m) {
         float a = load1(sv.a(m, i));
         float th = load1(theta + m * stride + i);
@@ -143,7 +152,7 @@ __device__ void eager_element(TT* theta, SV sv, int M, int64_t stride, int64_t i
         }
         store1(sv.p(m, i), sent(d, sc));
     }
-    store1(sv.d(i), dbar);
+    if (!sc.no_mean) store1(sv.d(i), dbar);
 }
 
 template <typename TT, int MODE, typename SV>
@@ -182,13 +191,26 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
         a[m] = load4(sv.a(m, i));
         d[m] = load4(theta + m * stride + i);  // theta for now
     }
+    const bool form_mean = MODE == MODE_EAGER && sc.no_mean;  // the previous mean from the previous locals
     if (MODE != MODE_RECORD) {
-        Dold = load4(sv.d(i));
+        if (!form_mean) Dold = load4(sv.d(i));
 #pragma unroll
         for (int m = 0; m < M; ++m) {
             u[m] = load4(sv.u(m, i));
             if (MODE == MODE_EAGER) p[m] = load4(sv.p(m, i));
         }
+    }
+    if (form_mean) {  // the sum the previous call took, in its order: the same bits it would have stored
+        double t0 = 0.0, t1 = 0.0, t2 = 0.0, t3 = 0.0;
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            t0 += (double)p[m].x;
+            t1 += (double)p[m].y;
+            t2 += (double)p[m].z;
+            t3 += (double)p[m].w;
+        }
+        Dold = f4{(float)(t0 * sc.inv_M_d), (float)(t1 * sc.inv_M_d), (float)(t2 * sc.inv_M_d),
+                  (float)(t3 * sc.inv_M_d)};
     }
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
     f4 th[M];
@@ -211,7 +233,7 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
     if (MODE == MODE_RECORD) {
 #pragma unroll
         for (int m = 0; m < M; ++m) store4(sv.a(m, i), th[m]);
-        store4(sv.d(i), dbar);
+        if (!sc.no_mean) store4(sv.d(i), dbar);
 #pragma unroll
         for (int m = 0; m < M; ++m) store4(sv.p(m, i), sent(d[m], sc));
         return;
@@ -226,7 +248,7 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
     for (int m = 0; m < M; ++m) store4(theta + m * stride + i, a[m]);
 #pragma unroll
     for (int m = 0; m < M; ++m) store4(sv.a(m, i), a[m]);
-    store4(sv.d(i), dbar);
+    if (!sc.no_mean) store4(sv.d(i), dbar);
 #pragma unroll
     for (int m = 0; m < M; ++m) {
         store4(sv.u(m, i), u[m]);
@@ -537,6 +559,7 @@ __global__ __launch_bounds__(kMaxBlock) void repack_kernel(float* tiled, float* 
 static bool parse_comm(int variant, OuterScalars& sc) {
     sc.comm = COMM_F32;
     sc.q_mant = sc.q_emin = sc.q_bias = 0;
+    sc.no_mean = 0;
     sc.q_max = 0.f;
     const bool bf16 = variant & DILOCO_COMM_BF16, exmy = variant & 0x200;
     if (bf16 && exmy) return false;
@@ -559,6 +582,7 @@ static OuterScalars make_scalars(int M, double lr, double mu, int nesterov) {
     OuterScalars sc;
     sc.comm = COMM_F32;
     sc.q_mant = sc.q_emin = sc.q_bias = 0;
+    sc.no_mean = 0;
     sc.q_max = 0.f;
     sc.mu = (float)mu;
     sc.c_g = nesterov ? (float)lr : 0.f;
@@ -591,7 +615,9 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
                            shape.lds, st, theta, sv, n, stride, sc, g.per_xcd);                           \
         return launch_status();                                                                           \
     }
-    switch (tuning().generic_path ? 0 : M) {  // a forced generic path also replaces the register kernels
+    // a forced generic path also replaces the register kernels, unless the call does without the
+    // stored mean, which only they know how to do
+    switch ((tuning().generic_path && !sc.no_mean) ? 0 : M) {
         DILOCO_REG_CASE(1)
         DILOCO_REG_CASE(2)
         DILOCO_REG_CASE(3)
@@ -654,9 +680,12 @@ extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, 
     if (!theta || !anchor || !vel || !prev_local || !prev_mean) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
     OuterScalars comm;
-    if (!parse_comm(variant, comm)) return DILOCO_ERR_DTYPE;
+    const int no_mean = (variant & DILOCO_STATE_NO_MEAN) ? 1 : 0;
+    if (!parse_comm(variant & ~DILOCO_STATE_NO_MEAN, comm)) return DILOCO_ERR_DTYPE;
     variant = static_cast<diloco_variant>(variant & 0xff);
     if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
+    if (no_mean && variant != DILOCO_EAGER) return DILOCO_ERR_DTYPE;
+    if (no_mean && M > kMaxRegisterReplicas) return DILOCO_ERR_SHAPE;
     if (int e = check_shape(M, n, stride)) return e;
     if (int e = check_shape(M, n, state_stride)) return e;
     if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
@@ -676,6 +705,7 @@ extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, 
                         (M == 1 || (stride % 4 == 0 && state_stride % 4 == 0));
     OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
     sc.comm = comm.comm, sc.q_mant = comm.q_mant, sc.q_emin = comm.q_emin, sc.q_bias = comm.q_bias, sc.q_max = comm.q_max;
+    sc.no_mean = no_mean;
     const RowState sv{anchor, vel, prev_local, prev_mean, state_stride};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)
@@ -695,9 +725,12 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
     if (!theta || !state) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
     OuterScalars comm;
-    if (!parse_comm(variant, comm)) return DILOCO_ERR_DTYPE;
+    const int no_mean = (variant & DILOCO_STATE_NO_MEAN) ? 1 : 0;
+    if (!parse_comm(variant & ~DILOCO_STATE_NO_MEAN, comm)) return DILOCO_ERR_DTYPE;
     variant = static_cast<diloco_variant>(variant & 0xff);
     if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
+    if (no_mean && variant != DILOCO_EAGER) return DILOCO_ERR_DTYPE;
+    if (no_mean && M > kMaxRegisterReplicas) return DILOCO_ERR_SHAPE;
     if (int e = check_shape(M, n, stride)) return e;
     if (n > ((int64_t)1 << 40)) return DILOCO_ERR_SHAPE;
     if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
@@ -709,6 +742,7 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
     const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
     OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
     sc.comm = comm.comm, sc.q_mant = comm.q_mant, sc.q_emin = comm.q_emin, sc.q_bias = comm.q_bias, sc.q_max = comm.q_max;
+    sc.no_mean = no_mean;
     const TiledState sv{state, (int64_t)M};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)

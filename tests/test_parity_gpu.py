@@ -676,7 +676,100 @@ def test_standard_outer_step_with_quantised_communication(M, comm, misalign):
     assert ei.value.status == d.binding.ERR_DTYPE
 
 
-@pytest.mark.parametrize("bits", [0x200, 0x400, 0x800, 1 << 28, 0x100 | 0x200 | (4 << 12) | (3 << 16),
+# ------------------------------------------------------------------ eager step that does not keep the previous mean
+@pytest.mark.parametrize("M", [1, 2, 3, 8])
+@pytest.mark.parametrize("layout,misalign,bf16", [("rows", 0, False), ("rows", 1, False), ("packed", 0, False),
+                                                   ("packed", 0, True)])
+@pytest.mark.parametrize("comm", [0, "bf16"])
+def test_eager_without_a_stored_mean_walks_the_same_trajectory_bit_for_bit(M, layout, misalign, bf16, comm):
+    """Five boundaries (the first only records) with and without DILOCO_STATE_NO_MEAN: the mean the
+    flagged calls form from prev_local is the one the plain calls stored, so every buffer but
+    the mean itself must agree exactly; the flagged run never touches its mean buffer."""
+    n = 24_579
+    wl = wl_for(M, n, bf16)
+    cflag = d.COMM_BF16 if comm == "bf16" else 0
+    runs = []
+    for flag in (0, d.STATE_NO_MEAN):
+        st = {k: v.to(DEV) for k, v in W.outer_state(wl, n, seed=103, stride=n + 8).items()}
+        g = {k: (v[:, misalign:misalign + n] if v.dim() == 2 else v) for k, v in st.items()}
+        g["prev_mean"].fill_(7.0)
+        for k in ("prev_local", "vel"):
+            st[k].zero_()
+        state = None
+        if layout == "packed":
+            state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+            d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                         prev_mean=g["prev_mean"])
+        for phase in range(5):
+            noise = W.normal((M, n), 1e-3, tag="theta_noise", seed=103, extra=phase, device=DEV)
+            g["theta"].copy_((g["theta"].float() + noise).to(g["theta"].dtype))
+            kw = dict(n=n, outer_lr=ETA, outer_momentum=MU, variant=d.EAGER | cflag | flag, apply_update=phase > 0)
+            if layout == "packed":
+                d.outer_eager_packed(g["theta"], state, **kw)
+            else:
+                d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], **kw)
+        if layout == "packed":
+            d.unpack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                           prev_mean=g["prev_mean"])
+        torch.cuda.synchronize()
+        runs.append(g)
+    plain, lean = runs
+    for k in ("theta", "anchor", "vel", "prev_local"):
+        assert torch.equal(plain[k], lean[k]), k
+    assert (lean["prev_mean"] == 7.0).all() and not (plain["prev_mean"] == 7.0).any()
+
+
+@pytest.mark.parametrize("M", [1, 2, 5, 8])
+@pytest.mark.parametrize("packed", [False, True])
+def test_eager_without_a_stored_mean_against_the_checker(M, packed):
+    n = 20_003
+    st = W.outer_state(wl_for(M, n), n, seed=107)
+    ref = {k: W.to_f64(v) for k, v in st.items()}
+    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], None, ETA, MU, True, True)
+    g = {k: v.to(DEV) for k, v in st.items()}
+    g["prev_mean"].fill_(-3.0)          # must not matter
+    if packed:
+        state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+        d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                     prev_mean=g["prev_mean"])
+        d.outer_eager_packed(g["theta"], state, outer_lr=ETA, outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
+        d.unpack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                       prev_mean=g["prev_mean"])
+    else:
+        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], outer_lr=ETA,
+                      outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
+    torch.cuda.synchronize()
+    for k in ("theta", "anchor", "vel", "prev_local"):
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"no stored mean M={M} {k}")
+    assert (g["prev_mean"] == -3.0).all()
+
+
+def test_eager_without_a_stored_mean_is_refused_where_it_cannot_work():
+    g = _rows(9, 64, 3)
+    with pytest.raises(d.DilocoError) as ei:      # no register kernel beyond 8 replicas
+        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], outer_lr=ETA,
+                      outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
+    assert ei.value.status == d.binding.ERR_SHAPE
+    g = _rows(2, 64, 3)
+    with pytest.raises(d.DilocoError) as ei:      # the delayed step reads nothing but the stored mean
+        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], outer_lr=ETA,
+                      outer_momentum=MU, variant=d.DELAYED | d.STATE_NO_MEAN)
+    assert ei.value.status == d.binding.ERR_DTYPE
+    d.tune("generic_path", 2)                      # a forced generic path gives way to the register kernel
+    try:
+        a, b = _rows(4, 4099, 5), _rows(4, 4099, 5)
+        d.outer_eager(a["theta"], a["anchor"], a["vel"], a["prev_local"], a["prev_mean"], outer_lr=ETA,
+                      outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
+    finally:
+        d.tune("generic_path", 0)
+    d.outer_eager(b["theta"], b["anchor"], b["vel"], b["prev_local"], b["prev_mean"], outer_lr=ETA,
+                  outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+
+
+@pytest.mark.parametrize("bits", [0x200, 0x800, 0x1000, 1 << 28, 0x100 | 0x200 | (4 << 12) | (3 << 16),
                                   "E0M3b0", "E9M1b0", "E5M11b0", "E8M7b127", "E8M2b100", "E4M3b-120", "E4M3b125", "E2M10b118", "E4M3b-113"])
 def test_unknown_variant_bits_are_rejected(bits):
     if isinstance(bits, str):
