@@ -32,14 +32,17 @@ class QuadraticSimulation:
     fragments: Streaming-DiLoCo windows [(offset, count), ...] on staggered boundaries.
     overlap: 1 (the listings) or 2 (2-outer-steps overlap; rows layout only).
     fused: run the inner steps between two outer boundaries as one pass over the buffers
-    (bit-identical to the step-by-step run)."""
+    (bit-identical to the step-by-step run).
+    no_mean: eager only, M <= 8: do not keep the previous mean, form it from the previous local
+    outer gradients (bit-identical as well)."""
 
     def __init__(self, M: int, n: int, H: int, variant: str = "eager", *, layout: str = "packed",
                  fragments: Optional[Sequence[Tuple[int, int]]] = None, overlap: int = 1,
                  comm_bf16: bool = False, comm_flags: int = 0, seed: int = W.BASE_SEED, noise_std: float = 0.1,
                  lr: float = 4e-4, beta1: float = 0.9, beta2: float = 0.95, eps: float = 1e-8,
                  weight_decay: float = 0.0, outer_lr: float = 0.7, outer_momentum: float = 0.9,
-                 nesterov: bool = True, fused: bool = False, device: str = "cuda:0"):
+                 nesterov: bool = True, fused: bool = False, no_mean: bool = False,
+                 device: str = "cuda:0"):
         assert variant in ("standard", "delayed", "eager")
         assert layout in ("packed", "rows") and overlap in (1, 2)
         self.M, self.n, self.H, self.variant = M, n, H, variant
@@ -52,6 +55,9 @@ class QuadraticSimulation:
         self.outer = dict(outer_lr=outer_lr, outer_momentum=outer_momentum, nesterov=nesterov)
         self.flags = ((B.DELAYED if variant == "delayed" else B.EAGER) | (B.COMM_BF16 if comm_bf16 else 0)
                       | comm_flags)      # comm_flags: e.g. binding.COMM_EXMY(2, 1, 11)
+        if no_mean:
+            assert variant == "eager" and overlap == 1, "only the eager step can do without the stored mean"
+            self.flags |= B.STATE_NO_MEAN
         self.fused = fused
         self.t = 0
         f32 = dict(dtype=torch.float32, device=device)
