@@ -53,6 +53,28 @@ def eager(lib, theta=P[0], dt=0, M=2, n=64, stride=64, a=P[1], u=P[2], pl=P[3], 
     return lib.diloco_outer_eager(theta, dt, M, n, stride, a, u, pl, ss, pm, lr, mu, nest, var, apply, None)
 
 
+def test_variant_flags_are_validated_before_any_launch(lib):
+    assert eager(lib, n=0, var=B.EAGER | B.STATE_NO_MEAN) == B.OK
+    assert eager(lib, var=B.DELAYED | B.STATE_NO_MEAN) == B.ERR_DTYPE
+    assert eager(lib, M=9, stride=64, var=B.EAGER | B.STATE_NO_MEAN) == B.ERR_SHAPE
+    assert eager(lib, var=B.EAGER | B.COMM_BF16 | B.COMM_EXMY(4, 3, 7)) == B.ERR_DTYPE
+    assert eager(lib, var=B.EAGER | B.COMM_EXMY(0, 3, 7)) == B.ERR_DTYPE
+    assert eager(lib, var=B.EAGER | B.COMM_EXMY(8, 7, 127)) == B.ERR_DTYPE     # below float32's normal range
+    assert eager(lib, n=0, var=B.EAGER | B.COMM_EXMY(2, 1, 11) | B.STATE_NO_MEAN) == B.OK
+    assert eager(lib, var=0x800) == B.ERR_DTYPE
+
+    def sync(comm, n=64):
+        return lib.diloco_outer_sync_comm(P[0], 0, 2, n, 64, P[1], P[2], None, 0.7, 0.9, 1, comm, None)
+    assert sync(0, n=0) == B.OK and sync(B.COMM_BF16, n=0) == B.OK and sync(B.COMM_EXMY(4, 3, 16), n=0) == B.OK
+    assert sync(1) == B.ERR_DTYPE and sync(B.STATE_NO_MEAN) == B.ERR_DTYPE and sync(B.COMM_EXMY(9, 1, 0)) == B.ERR_DTYPE
+
+    def rmw(K=4, n=64, stride=64, base=P[0]):
+        return lib.diloco_sim_stream_rmw(base, K, n, stride, None)
+    assert rmw(n=0) == B.OK
+    assert rmw(K=3) == B.ERR_SHAPE and rmw(n=62) == B.ERR_SHAPE and rmw(stride=32) == B.ERR_SHAPE
+    assert rmw(base=None) == B.ERR_NULL and rmw(base=P[0] + 4) == B.ERR_ALIGN and rmw(stride=66) == B.ERR_ALIGN
+
+
 def test_outer_eager_validation(lib):
     assert eager(lib, n=0) == B.OK                      # empty input: no-op, nothing launched
     assert eager(lib, theta=None) == B.ERR_NULL
