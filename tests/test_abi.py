@@ -242,3 +242,34 @@ def test_binding_raises_with_status_text(lib):
 
 class _NullStream:
     cuda_stream = 0
+
+
+def test_headers_are_plain_c_and_a_c_program_links_against_the_library(lib, tmp_path):
+    """The boundary is a C ABI: both headers must compile as C99 on their own, and a C program
+    that includes them must link against the shared library and call it."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler here")
+    inc = os.path.join(ROOT, "include")
+    for hdr in ("diloco.h", "diloco_sim.h"):
+        subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(inc, hdr)], check=True)
+    src = tmp_path / "probe.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "diloco.h"\n#include "diloco_sim.h"\n'
+        "int main(void) {\n"
+        "    /* validation only: no launch, no GPU needed */\n"
+        "    int rc = diloco_outer_eager(NULL, DILOCO_F32, 2, 64, 64, NULL, NULL, NULL, 64, NULL, 0.7, 0.9, 1,\n"
+        "                                (diloco_variant)(DILOCO_EAGER | DILOCO_COMM_EXMY(2, 1, 11)), 1, NULL);\n"
+        '    printf("%d %d %s %lld %d\\n", diloco_version(), rc, diloco_strerror(rc),\n'
+        "           (long long)diloco_packed_state_elems(8, 8193), DILOCO_SIM_MAX_FUSED_STEPS);\n"
+        "    return 0;\n}\n")
+    exe = tmp_path / "probe"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe), "-L", libdir,
+                    "-l:" + os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=2)
+    assert int(out[0]) >= 100 and int(out[1]) == B.ERR_NULL
+    assert out[2].strip().endswith(f"{2 * 25 * 8192} 64")
