@@ -860,3 +860,115 @@ def test_every_launch_shape_gives_the_same_bits(launch_shape):
     assert_close(W.to_f64(ga), ra, TOL_F32, "sync anchor")
     assert_close(W.to_f64(gu), ru, TOL_F32, "sync vel")
     assert torch.equal(gt, ga.expand(3, n)) and torch.equal(th2, gt)
+
+
+# ------------------------------------------------------------------ seeded sweep over valid argument combinations
+def _random_case(rng):
+    M = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 11, 17, 42]))
+    n = int(rng.choice([1, 3, 4, 63, 64, 257, 1000, 4097, 8191, 8192, 8193, 20_001]))
+    variant = str(rng.choice(["eager", "delayed"]))
+    case = dict(M=M, n=n, variant=variant, apply=bool(rng.integers(0, 2)), nesterov=bool(rng.integers(0, 2)),
+                bf16=bool(rng.integers(0, 2)), packed=bool(rng.integers(0, 2)), pad=int(rng.choice([0, 1, 4, 6])),
+                comm=[None, "bf16", (2, 1, 11), (4, 3, 16), (5, 2, 24)][int(rng.integers(0, 5))],
+                no_mean=bool(rng.integers(0, 2)) and variant == "eager" and M <= 8,
+                shape=[(0, 0, -1), (64, 1, 2), (256, 0, 0), (128, 1, 3), (512, 0, 1)][int(rng.integers(0, 5))],
+                eta=float(rng.choice([0.7, 1.0, 0.1])), mu=float(rng.choice([0.9, 0.0, 0.5])))
+    case["misalign"] = 0 if case["packed"] else int(rng.choice([0, 0, 1, 2]))
+    return case
+
+
+@pytest.mark.parametrize("chunk", range(8))
+def test_seeded_sweep_of_valid_eager_calls_matches_the_checker(chunk):
+    """25 argument combinations per chunk, drawn from a fixed seed: replica counts on every kernel
+    path, ragged and tiny sizes, both layouts, misaligned rows, bf16 replicas, every wire format,
+    with and without the stored mean, first boundary or not, several launch shapes."""
+    rng = np.random.default_rng(1000 + chunk)
+    for _ in range(25):
+        c = _random_case(rng)
+        M, n, mis = c["M"], c["n"], c["misalign"]
+        wl = wl_for(M, n, c["bf16"])
+        stride = ((n + c["pad"] + mis + 3) & ~3) if c["packed"] else n + c["pad"] + mis
+        cut = (lambda v: v[:, mis:mis + n] if v.dim() == 2 else v)
+        host = W.outer_state(wl, n, seed=300 + chunk, stride=stride)
+        ref = {k: W.to_f64(cut(v)) for k, v in host.items()}
+        comm = "f32" if c["comm"] is None else ("bf16" if c["comm"] == "bf16" else ("exmy",) + c["comm"])
+        fn = O.outer_eager if c["variant"] == "eager" else O.outer_delayed
+        if c["no_mean"]:
+            O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], None, c["eta"], c["mu"],
+                          c["nesterov"], c["apply"], comm=comm)
+        else:
+            fn(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], c["eta"], c["mu"],
+               c["nesterov"], c["apply"], comm=comm)
+        full = {k: v.to(DEV) for k, v in host.items()}
+        g = {k: cut(v) for k, v in full.items()}
+        before_mean = g["prev_mean"].clone()
+        flags = (d.EAGER if c["variant"] == "eager" else d.DELAYED) | (d.STATE_NO_MEAN if c["no_mean"] else 0)
+        if c["comm"] is not None:
+            flags |= d.COMM_BF16 if c["comm"] == "bf16" else d.COMM_EXMY(*c["comm"])
+        kw = dict(n=n, outer_lr=c["eta"], outer_momentum=c["mu"], nesterov=c["nesterov"], variant=flags,
+                  apply_update=c["apply"])
+        set_shape(*c["shape"])
+        try:
+            if c["packed"]:
+                state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+                d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                             prev_mean=g["prev_mean"])
+                d.outer_eager_packed(g["theta"], state, **kw)
+                d.unpack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                               prev_mean=g["prev_mean"])
+            else:
+                d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], **kw)
+        finally:
+            set_shape(*DEFAULT_SHAPE)
+        torch.cuda.synchronize()
+        for k in ref:
+            if k == "prev_mean" and c["no_mean"]:
+                assert torch.equal(g[k], before_mean), c
+                continue
+            tol = TOL_BF16 if (c["bf16"] and k == "theta") else TOL_F32
+            assert_close(W.to_f64(g[k]), ref[k], tol, f"{c} {k}")
+        if c["comm"] is not None:
+            assert np.array_equal(W.to_f64(g["prev_local"]), ref["prev_local"]), c
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_seeded_sweep_of_valid_standard_and_adamw_calls_matches_the_checker(chunk):
+    rng = np.random.default_rng(2000 + chunk)
+    for _ in range(20):
+        M = int(rng.choice([1, 2, 3, 4, 7, 8, 9, 12, 16, 33]))
+        n = int(rng.choice([1, 3, 4, 64, 257, 4097, 8193, 20_001]))
+        bf16, mis, pad = bool(rng.integers(0, 2)), int(rng.choice([0, 0, 1, 3])), int(rng.choice([0, 1, 4]))
+        comm = [None, "bf16", (2, 1, 11), (4, 3, 16)][int(rng.integers(0, 4))]
+        shape = [(0, 0, -1), (64, 1, 2), (256, 0, 0), (128, 1, 3), (512, 0, 1)][int(rng.integers(0, 5))]
+        eta, mu, nest = float(rng.choice([0.7, 1.0])), float(rng.choice([0.9, 0.0])), bool(rng.integers(0, 2))
+        wl = wl_for(M, n, bf16)
+        cut = (lambda v: v[:, mis:mis + n])
+        host = W.outer_state(wl, n, seed=400 + chunk, stride=n + pad + mis)
+        a, u = host["anchor"][0, :n].clone(), host["vel"][0, :n].clone()
+        rt, ra, ru = W.to_f64(cut(host["theta"])), W.to_f64(a), W.to_f64(u)
+        want = O.outer_standard(rt, ra, ru, eta, mu, nest,
+                                comm="f32" if comm is None else ("bf16" if comm == "bf16" else ("exmy",) + comm))
+        gt = cut(host["theta"].to(DEV))
+        ga, gu, gm = a.to(DEV), u.to(DEV), torch.zeros(n, device=DEV)
+        ad = W.adamw_state(wl, n, seed=500 + chunk, stride=n + pad + mis,
+                           grad_dtype=torch.bfloat16 if (bf16 and rng.integers(0, 2)) else torch.float32)
+        refa = {k: W.to_f64(cut(v)) for k, v in ad.items()}
+        step = int(rng.choice([1, 2, 31, 1000]))
+        O.adamw_step(refa["theta"], refa["m1"], refa["m2"], refa["grad"], step, 4e-4, 0.9, 0.95, 1e-8, 0.1)
+        gad = {k: cut(v.to(DEV)) for k, v in ad.items()}
+        set_shape(*shape)
+        try:
+            d.outer_sync(gt, ga, gu, n=n, mean_out=gm, outer_lr=eta, outer_momentum=mu, nesterov=nest,
+                         comm=None if comm is None else (d.COMM_BF16 if comm == "bf16" else d.COMM_EXMY(*comm)))
+            d.inner_adamw(gad["theta"], gad["m1"], gad["m2"], gad["grad"], n=n, lr=4e-4, beta1=0.9, beta2=0.95,
+                          eps=1e-8, weight_decay=0.1, step=step)
+        finally:
+            set_shape(*DEFAULT_SHAPE)
+        torch.cuda.synchronize()
+        tag = f"M={M} n={n} bf16={bf16} mis={mis} comm={comm} shape={shape}"
+        assert_close(W.to_f64(gm), want, TOL_F32, f"standard mean {tag}")
+        assert_close(W.to_f64(ga), ra, TOL_F32, f"standard anchor {tag}")
+        assert_close(W.to_f64(gu), ru, TOL_F32, f"standard vel {tag}")
+        assert torch.equal(gt, ga.to(gt.dtype).expand(M, n)), tag
+        for k in ("theta", "m1", "m2"):
+            assert_close(W.to_f64(gad[k]), refa[k], TOL_BF16 if bf16 else TOL_F32, f"adamw {k} {tag} step={step}")
