@@ -699,3 +699,26 @@ def test_overlap_one_is_the_listing():
         np.testing.assert_array_equal(s1[k], s2[k])
     s3, _ = O.run_quadratic("eager", overlap=2, **kw)
     assert np.max(np.abs(s3["a"] - s1["a"])) > 0
+
+
+# ------------------------------------------------ frozen outputs of the checker itself ---
+def test_checker_outputs_have_not_drifted_from_the_frozen_runs():
+    """tests/golden/checker_trajectories.txt was written by tests/golden/make_golden.py from the
+    checker alone.  It pins nothing to the paper (the tests above do that); it makes a change to
+    the checker's arithmetic visible, so that it is made on purpose and justified."""
+    import importlib.util
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    frozen = {}
+    for line in open(os.path.join(here, "checker_trajectories.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, *vals = line.split()
+        frozen[name] = np.array([float.fromhex(v) for v in vals])
+    now = mod.runs()
+    assert set(now) == set(frozen)
+    for name, want in frozen.items():
+        # libm's log / sin / cos may differ in the last place between machines: 1e-13, not bit equality
+        np.testing.assert_allclose(now[name], want, rtol=1e-13, atol=1e-300, err_msg=name)
