@@ -972,3 +972,50 @@ def test_seeded_sweep_of_valid_standard_and_adamw_calls_matches_the_checker(chun
         assert torch.equal(gt, ga.to(gt.dtype).expand(M, n)), tag
         for k in ("theta", "m1", "m2"):
             assert_close(W.to_f64(gad[k]), refa[k], TOL_BF16 if bf16 else TOL_F32, f"adamw {k} {tag} step={step}")
+
+
+# ------------------------------------------------------------------ HIP graph capture
+def test_a_captured_step_replays_to_the_same_bits():
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no
+    synchronisation, no memset), so a step can be captured into a HIP graph.  Three replays, with
+    ordinary launches and synchronisations between them, against the same steps launched directly."""
+    M, n = 8, 150_003
+    wl = wl_for(M, n)
+
+    def fresh():
+        st = {k: v.to(DEV) for k, v in W.outer_state(wl, n, seed=113, stride=n + 1).items()}
+        ad = {k: v.to(DEV) for k, v in W.adamw_state(wl, n, seed=113, stride=n + 1).items()}
+        state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+        d.pack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
+                     prev_mean=st["prev_mean"])
+        return st["theta"], ad["m1"], ad["m2"], ad["grad"], state
+
+    def step(theta, m1, m2, grad, state):
+        d.inner_adamw(theta, m1, m2, grad, n=n, lr=4e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=7)
+        d.outer_eager_packed(theta, state, n=n, outer_lr=ETA, outer_momentum=MU)
+        d.outer_eager_packed(theta, state, n=n, outer_lr=ETA, outer_momentum=MU,
+                             variant=d.EAGER | d.STATE_NO_MEAN | d.COMM_BF16)
+
+    direct = fresh()
+    for _ in range(3):
+        step(*direct)
+    torch.cuda.synchronize()
+
+    bufs = fresh()
+    warm = fresh()
+    step(*warm)                      # first launches (and their one-time LDS grants) outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(*bufs)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for k in range(3):
+        graph.replay()
+        scratch.add_(1.0)            # the program's own eager work between replays
+        torch.cuda.synchronize()
+    for x, y, name in zip(direct, bufs, ("theta", "m1", "m2", "grad", "state")):
+        assert torch.equal(x, y), name
