@@ -79,10 +79,27 @@ def cpu_baseline(wl, sample, min_seconds=10.0, max_reps=16):
         outer_s += t2 - t1
         reps += 1
         assert np.isfinite(st["anchor"]).all()
+    # the standard outer step once, outside the headline figure
+    th, a, u = st0["theta"].copy(), st0["anchor"][0].copy(), st0["vel"][0].copy()
+    t0 = time.perf_counter()
+    O.outer_standard(th, a, u, wl.outer_lr, wl.outer_momentum, True)
+    standard_s = time.perf_counter() - t0
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     return dict(value=reps * sample / (inner_s + outer_s), unit="params/s", cores=1, kind="oracle",
                 sample=f"{reps} x {sample} parameter indices x M={wl.M} replicas of {wl.name}: AdamW sweep "
                        f"({inner_s:.2f} s) + eager outer step ({outer_s:.2f} s), float64 NumPy, 1 thread",
-                inner_s=inner_s, outer_s=outer_s, outer_params_per_s=reps * sample / outer_s)
+                inner_s=inner_s, outer_s=outer_s, outer_params_per_s=reps * sample / outer_s,
+                inner_worker_params_per_s=reps * sample * wl.M / inner_s,
+                standard_outer_params_per_s=sample / standard_s,
+                host_cpus=os.cpu_count(), cpu_model=cpu_model)
 
 
 def main():
