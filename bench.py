@@ -384,6 +384,8 @@ def main():
                      "frac_of_stream_rmw": None if rmw_gbps is None else outer_gbps / rmw_gbps,
                      "traffic": stored_traffic(wl.name, args.layout)},
     }
+    if result["roofline"]["traffic"]:   # counter bytes over this run's time: the rate the counters imply
+        result["roofline"]["traffic_GBps"] = result["roofline"]["traffic"] / (outer_ms * 1e-3) / 1e9
     del st, ad, theta, m1, m2, grad
     if packed:
         del state
