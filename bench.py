@@ -33,7 +33,16 @@ def algorithmic_bytes(wl, n):
 
 
 def shape_json(sh):
+    if sh is None:
+        return "automatic"
     return {"block": sh[0], "xcd_remap": sh[1], "wg_per_cu": sh[2]}
+
+
+def spread(ms):
+    """min / median / max / mean of per-launch times in ms."""
+    s = sorted(ms)
+    return {"min": s[0], "median": s[len(s) // 2] if len(s) % 2 else 0.5 * (s[len(s) // 2 - 1] + s[len(s) // 2]),
+            "max": s[-1], "mean": sum(s) / len(s)}
 
 
 def outer_bytes_fn(wl, n):
@@ -150,46 +159,39 @@ def main():
         torch.cuda.synchronize()
         return sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(iters))
 
-    def set_shape(sh):
-        d.tune("block", sh[0])
-        d.tune("xcd_remap", sh[1])
-        d.tune("wg_per_cu", sh[2])
-
-    # (workgroup size, XCD-contiguous workgroup order, cap on resident workgroups per CU); block 0
-    # and cap -1 leave the choice to the launch itself
-    shape_default = (0, 0, -1)
+    # Launch shapes travel with each call (the *_shaped entry points): (workgroup size, XCD-contiguous
+    # workgroup order, cap on resident workgroups per CU); None, or block 0 and cap -1, leave the
+    # choice to the launch itself.  Nothing outside the call holds a shape.
+    shape_default = None
     candidates = ([(0, x, -1) for x in (0, 1)]
                   + [(64, x, c) for x in (0, 1) for c in (2, 3, 4, 6, 8, 12, 16)]
                   + [(256, x, c) for x in (0, 1) for c in (0, 1, 2, 3)]
                   + [(b, x, 0) for x in (0, 1) for b in (128, 512)])
 
     def autotune(fn):
-        """Fastest of the launch shapes the library offers, by median of 5."""
+        """Fastest of the launch shapes the library offers, by median of 5; fn(shape) launches once."""
         best = None
         for sh in candidates:
-            set_shape(sh)
-            fn()
-            t = timed(fn, 5)[2]
+            fn(sh)
+            t = timed(lambda: fn(sh), 5)[2]
             if best is None or t < best[0]:
                 best = (t, sh)
-        set_shape(shape_default)
         return best[1]
 
-    def run_rows():
-        d.outer_eager(theta, st["anchor"], st["vel"], st["prev_local"], st["prev_mean"], n=n, **okw)
+    def run_rows(sh=None):
+        d.outer_eager(theta, st["anchor"], st["vel"], st["prev_local"], st["prev_mean"], n=n, launch=sh, **okw)
 
-    def run_inner(t=31):
+    def run_inner(sh=None, t=31):
         d.inner_adamw(theta, m1, m2, grad, n=n, lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps,
-                      weight_decay=wl.weight_decay, step=t)
+                      weight_decay=wl.weight_decay, step=t, launch=sh)
 
     shape_rows = autotune(run_rows) if args.autotune else shape_default
     shape_inner = autotune(run_inner) if args.autotune else shape_default
 
     # the eager step on caller-layout rows, timed on its own (secondary figure)
-    set_shape(shape_rows)
-    run_rows()
-    rows_ms = timed(run_rows, max(3, args.steps // 2))
-    rows_ms = sum(rows_ms) / len(rows_ms)
+    run_rows(shape_rows)
+    rows_all = timed(lambda: run_rows(shape_rows), max(5, args.steps // 2))
+    rows_ms = sum(rows_all) / len(rows_all)
 
     packed = args.layout == "packed"
     if packed:
@@ -201,8 +203,8 @@ def main():
             del st[k]
         torch.cuda.empty_cache()
 
-        def run_outer():
-            d.outer_eager_packed(theta, state, n=n, **okw)
+        def run_outer(sh=None, **kw):
+            d.outer_eager_packed(theta, state, n=n, launch=sh, **okw, **kw)
         shape_outer = autotune(run_outer) if args.autotune else shape_default
     else:
         run_outer, shape_outer = run_rows, shape_rows
@@ -210,12 +212,10 @@ def main():
     def step(t, ev=None):
         if ev:
             ev[0].record()
-        set_shape(shape_inner)
-        run_inner(t)
+        run_inner(shape_inner, t)
         if ev:
             ev[1].record()
-        set_shape(shape_outer)
-        run_outer()
+        run_outer(shape_outer)
         if ev:
             ev[2].record()
 
@@ -231,8 +231,10 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / args.steps
-    inner_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
-    outer_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    inner_all = [e[0].elapsed_time(e[1]) for e in events]
+    outer_all = [e[1].elapsed_time(e[2]) for e in events]
+    inner_ms = sum(inner_all) / args.steps      # the average launch duration: what the roofline figure uses
+    outer_ms = sum(outer_all) / args.steps
     if packed:
         chk = torch.empty((M, 4096), device=dev)
         d.unpack_state(state, M, 4096, anchor=chk)
@@ -244,38 +246,37 @@ def main():
     # launch per group of 3 layers) and with bf16 outer gradients on the wire
     extra = {}
     if packed and wl.layers:
-        set_shape(shape_outer)
         frs = W.fragments(wl.layers, wl.d_model, wl.vocab)
 
         def run_fragments():
             for off, cnt in frs:
-                d.outer_eager_packed(theta[:, off:off + cnt], d.packed_window(state, M, off), n=cnt, **okw)
+                d.outer_eager_packed(theta[:, off:off + cnt], d.packed_window(state, M, off), n=cnt,
+                                     launch=shape_outer, **okw)
         run_fragments()
         fms = timed(run_fragments, 5)[2]
         extra["outer_step_by_fragments"] = {"fragments": len(frs), "ms": fms,
                                             "GBps": outer_bytes_fn(wl, n) / (fms * 1e-3) / 1e9}
 
         def run_q():
-            d.outer_eager_packed(theta, state, n=n, variant=d.EAGER | d.COMM_BF16, **okw)
+            run_outer(shape_outer, variant=d.EAGER | d.COMM_BF16)
         run_q()
         qms = timed(run_q, 5)[2]
         extra["outer_step_bf16_comm"] = {"ms": qms, "GBps": outer_bytes_fn(wl, n) / (qms * 1e-3) / 1e9}
 
         def run_q4():   # float4 (E2M1, range placed at the outer gradients' scale) on the wire
-            d.outer_eager_packed(theta, state, n=n, variant=d.EAGER | d.COMM_EXMY(2, 1, 11), **okw)
+            run_outer(shape_outer, variant=d.EAGER | d.COMM_EXMY(2, 1, 11))
         run_q4()
         q4ms = timed(run_q4, 5)[2]
         extra["outer_step_fp4_comm"] = {"ms": q4ms, "GBps": outer_bytes_fn(wl, n) / (q4ms * 1e-3) / 1e9}
 
-    if packed and M <= 8:
+    if packed:
         # the previous mean formed from the previous local outer gradients instead of kept: one
         # stream of 4M+1 less each way, priced at its own bytes
-        set_shape(shape_outer)
         es_ = 2 if bf16 else 4
         lean_bytes = 2 * (M * es_ + 12 * M) * n
 
         def run_lean():
-            d.outer_eager_packed(theta, state, n=n, variant=d.EAGER | d.STATE_NO_MEAN, **okw)
+            run_outer(shape_outer, variant=d.EAGER | d.STATE_NO_MEAN)
         run_lean()
         lms = timed(run_lean, 7)[3]
         extra["outer_step_no_stored_mean"] = {"ms": lms, "bytes_per_index": lean_bytes // n,
@@ -287,19 +288,17 @@ def main():
     sa = W.normal((n,), wl.std_anchor, tag="anchor", device=dev)
     sv = torch.zeros(n, dtype=torch.float32, device=dev)
 
-    def run_sync():
-        d.outer_sync(theta, sa, sv, **okw)
+    def run_sync(sh=None):
+        d.outer_sync(theta, sa, sv, launch=sh, **okw)
     shape_sync = autotune(run_sync) if args.autotune else shape_default
-    set_shape(shape_sync)
-    run_sync()
-    sms = timed(run_sync, 7)[3]
+    run_sync(shape_sync)
+    sms = timed(lambda: run_sync(shape_sync), 7)[3]
     extra["outer_step_standard"] = {"ms": sms, "GBps": (2 * M * es + 16) * n / (sms * 1e-3) / 1e9,
                                     "launch": shape_json(shape_sync)}
     del sa, sv
 
     # the stand-in training problem (configuration 5's shape): one inner step with the gradient made
     # in the kernel (HBM-bound), and a whole phase of H steps in one pass (vector-ALU-bound)
-    set_shape(shape_default)
     ql = W.WORKLOADS["quadratic"]
     qt = torch.zeros((ql.M, ql.n), dtype=torch.float32, device=dev)
     q1, q2 = torch.zeros_like(qt), torch.zeros_like(qt)
@@ -323,12 +322,10 @@ def main():
     src, dst = cbuf[:n], cbuf[n:]
     copy_ms = None
     for sh in [(b, x, 0) for b in (64, 256, 512) for x in (0, 1)]:
-        set_shape(sh)
         for _ in range(3):
-            d.sim_stream_copy(dst, src)
-        t = timed(lambda: d.sim_stream_copy(dst, src), 10)[5]
+            d.sim_stream_copy(dst, src, launch=sh)
+        t = timed(lambda: d.sim_stream_copy(dst, src, launch=sh), 10)[5]
         copy_ms = t if copy_ms is None else min(copy_ms, t)
-    set_shape(shape_default)
     copy_gbps = 8 * n / (copy_ms * 1e-3) / 1e9
     del cbuf, src, dst
 
@@ -340,21 +337,31 @@ def main():
         nr = min(n & ~3, 1 << 28)
         rbuf = torch.empty((K, nr), dtype=torch.float32, device=dev).normal_(0, 1e-3)
         for sh in [(0, x, -1) for x in (0, 1)] + [(64, x, c) for x in (0, 1) for c in (2, 3, 4, 6, 8)]:
-            set_shape(sh)
-            d.sim_stream_rmw(rbuf)
-            t = timed(lambda: d.sim_stream_rmw(rbuf), 5)[2]
+            d.sim_stream_rmw(rbuf, launch=sh)
+            t = timed(lambda: d.sim_stream_rmw(rbuf, launch=sh), 5)[2]
             g = 8 * K * nr / (t * 1e-3) / 1e9
             if rmw_gbps is None or g > rmw_gbps:
                 rmw_gbps, shape_rmw = g, sh
-        set_shape(shape_default)
         del rbuf
 
     outer_bytes, inner_bytes = algorithmic_bytes(wl, n)
     outer_gbps = outer_bytes / (outer_ms * 1e-3) / 1e9
     inner_gbps = inner_bytes / (inner_ms * 1e-3) / 1e9
+
+    def rates(ms, nbytes):
+        """Per-launch time spread with the rate and the fraction of peak each time stands for."""
+        sp = spread(ms)
+        return {"ms": sp, "GBps": {k: nbytes / (v * 1e-3) / 1e9 for k, v in sp.items()},
+                "frac_of_peak": {k: nbytes / (v * 1e-3) / 1e9 / HBM_PEAK_GBPS for k, v in sp.items()}}
+
+    outer_spread, inner_spread, rows_spread = rates(outer_all, outer_bytes), rates(inner_all, inner_bytes), \
+        rates(rows_all, outer_bytes)
     result = {
         "metric": "outer-step params/sec and achieved HBM GB/s (% of peak) at M workers",
-        "value": n / (ms_step * 1e-3),
+        # the metric is the outer step's: model parameters through one fused eager outer step per
+        # second, from the average duration of the outer kernel inside the timed step loop
+        "value": n / (outer_ms * 1e-3),
+        "value_is": "N / (average duration of the eager outer-step kernel inside the timed steps)",
         "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -365,14 +372,16 @@ def main():
                    "M": M, "N": n, "theta_dtype": wl.theta_dtype, "stride_pad": args.pad,
                    "outer_state_layout": args.layout,
                    "launch": {"outer": shape_json(shape_outer), "inner": shape_json(shape_inner)}},
+        "whole_step": {"ms": ms_step, "params_per_s": n / (ms_step * 1e-3),
+                       "what": "one AdamW sweep + one eager outer step, host clock over the timed steps"},
         "outer_step": {"ms": outer_ms, "params_per_s": n / (outer_ms * 1e-3),
                        "worker_params_per_s": M * n / (outer_ms * 1e-3), "GBps": outer_gbps,
-                       "frac_of_peak": outer_gbps / HBM_PEAK_GBPS},
+                       "frac_of_peak": outer_gbps / HBM_PEAK_GBPS, "per_step": outer_spread},
         "outer_step_rows_layout": {"ms": rows_ms, "GBps": outer_bytes / (rows_ms * 1e-3) / 1e9,
                                    "frac_of_peak": outer_bytes / (rows_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                                   "launch": shape_json(shape_rows)},
+                                   "per_launch": rows_spread, "launch": shape_json(shape_rows)},
         "inner_step": {"ms": inner_ms, "worker_params_per_s": M * n / (inner_ms * 1e-3),
-                       "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS},
+                       "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS, "per_step": inner_spread},
         **extra,
         "copy_ceiling_GBps": copy_gbps,
         "stream_rmw_ceiling": None if rmw_gbps is None else {"K": K, "GBps": rmw_gbps,
@@ -380,6 +389,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "outer_eager_reg_kernel<%d, %s, eager, %s>" % (
                          M, "bf16" if bf16 else "float", "TiledState" if packed else "RowState"), "achieved": outer_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": outer_gbps / HBM_PEAK_GBPS,
+                     "frac_min_median_max": [outer_spread["frac_of_peak"][k] for k in ("max", "median", "min")],
                      "frac_of_copy": outer_gbps / copy_gbps,
                      "frac_of_stream_rmw": None if rmw_gbps is None else outer_gbps / rmw_gbps,
                      "traffic": stored_traffic(wl.name, args.layout)},

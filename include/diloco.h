@@ -45,7 +45,9 @@ extern "C" {
 
 typedef enum { DILOCO_F32 = 0, DILOCO_BF16 = 1 } diloco_dtype;
 
-/* Which outer gradient OuterOpt is fed (diloco_outer_eager). */
+/* Which outer gradient OuterOpt is fed (diloco_outer_eager).  The `variant` argument is an int:
+ * one of these two values in its low byte, with the DILOCO_COMM_* / DILOCO_STATE_* flag bits
+ * below OR-ed in (an enum-typed parameter could not legally hold those bits). */
 typedef enum {
     DILOCO_EAGER = 0,   /* Algorithm 3 line 11: (Delta_m - Delta_m_prev)/M + Delta_prev */
     DILOCO_DELAYED = 1  /* Algorithm 2 line 11: Delta_prev                              */
@@ -87,7 +89,8 @@ typedef enum {
  * results are bit-identical to the flag-less calls as long as every call of a run carries the
  * flag or prev_mean is that mean.  One stream of 4M+1 less each way (11 % of the traffic at
  * M = 2, 3 % at M = 8).  EAGER only (DILOCO_ERR_DTYPE with DELAYED, which never reads
- * prev_local); M <= 8 (DILOCO_ERR_SHAPE beyond); prev_mean must still be a valid pointer.
+ * prev_local); any M (beyond 8 replicas the first 24 keep their prev_local on chip between the
+ * two sums, the others' is read twice); prev_mean must still be a valid pointer.
  */
 #define DILOCO_STATE_NO_MEAN 0x400
 
@@ -173,7 +176,7 @@ int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, int64_t n, 
                        float* anchor, float* vel, float* prev_local, int64_t state_stride,
                        float* prev_mean,
                        double outer_lr, double outer_momentum, int nesterov,
-                       diloco_variant variant, int apply_update, void* stream);
+                       int variant, int apply_update, void* stream);
 
 /*
  * Packed outer state.  The eager / delayed outer step touches 3M+1 state streams per
@@ -211,7 +214,7 @@ int diloco_unpack_state(const float* state, int M, int64_t n, float* anchor, flo
 int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
                               int64_t stride, float* state,
                               double outer_lr, double outer_momentum, int nesterov,
-                              diloco_variant variant, int apply_update, void* stream);
+                              int variant, int apply_update, void* stream);
 
 /* theta_m <- outer parameters of replica m, read from the packed state. */
 int diloco_reset_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,

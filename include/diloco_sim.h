@@ -20,6 +20,8 @@
 
 #include <stdint.h>
 
+#include "diloco.h"
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -68,12 +70,59 @@ int diloco_sim_quadratic_loss(const float* theta, int M, int64_t n, int64_t stri
                               void* stream);
 
 /*
+ * Launch shape of one call, for measurements.  The entry points of diloco.h choose their shape
+ * themselves; the *_shaped variants below run the same call (same validation, same kernels, same
+ * results bit for bit) in the shape the caller names, so that a harness can compare shapes
+ * without any state outside the call.  launch == NULL means the automatic choice.
+ *   block         threads per workgroup of the streaming kernels: 64..512, a power of two; 0 lets
+ *                 the launch choose (one-wavefront workgroups, throttled as wg_per_cu -1 says).
+ *   xcd_remap     0/1: give each of the 8 XCDs a contiguous slice of the index space.
+ *   wg_per_cu     at most this many workgroups of the kernel resident on a compute unit (1..32,
+ *                 enforced with dynamic LDS the kernel never touches); 0: no cap; -1: with block 0
+ *                 the cap that puts about 32-64 KB of loads in flight per compute unit, with an
+ *                 explicit block no cap.
+ *   generic_path  eager step only: 0 = register-resident kernel for M <= 8, beyond that the first
+ *                 40 replicas staged in LDS and the rest read twice; 1 = for every M, up to 80
+ *                 staged; 2 = for every M, none staged.
+ * A field out of range is DILOCO_ERR_HYPER.
+ */
+typedef struct diloco_launch {
+    int block;
+    int xcd_remap;
+    int wg_per_cu;
+    int generic_path;
+} diloco_launch;
+
+int diloco_inner_adamw_shaped(void* theta, void* m1, void* m2, const void* grad,
+                              int M, int64_t n, int64_t stride,
+                              diloco_dtype param_dtype, diloco_dtype grad_dtype,
+                              double lr, double beta1, double beta2, double eps,
+                              double weight_decay, int64_t step, void* stream,
+                              const diloco_launch* launch);
+int diloco_outer_sync_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                             float* anchor, float* vel, float* mean_out,
+                             double outer_lr, double outer_momentum, int nesterov, int comm,
+                             void* stream, const diloco_launch* launch);
+int diloco_outer_eager_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
+                              float* anchor, float* vel, float* prev_local, int64_t state_stride,
+                              float* prev_mean,
+                              double outer_lr, double outer_momentum, int nesterov,
+                              int variant, int apply_update, void* stream,
+                              const diloco_launch* launch);
+int diloco_outer_eager_packed_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                     int64_t stride, float* state,
+                                     double outer_lr, double outer_momentum, int nesterov,
+                                     int variant, int apply_update, void* stream,
+                                     const diloco_launch* launch);
+
+/*
  * Measurement aid: dst[i] <- src[i] for n fp32 elements with the same 128-bit
  * non-temporal accesses and launch shape as the sweep kernels (moves 8n bytes).  The
  * rate it reaches is the practical HBM ceiling the sweeps are compared with.
- * dst, src: 16-byte aligned, non-overlapping.
+ * dst, src: 16-byte aligned, non-overlapping.  launch: as above, NULL = automatic.
  */
-int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream);
+int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream,
+                           const diloco_launch* launch);
 
 /*
  * In-place sweep over K rows of n floats, `stride` floats apart: each 16-byte piece of every
@@ -81,24 +130,18 @@ int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream
  * touches all K rows at one index).  No arithmetic: the rate it reaches is what the memory
  * system gives a read-modify-write over K separated streams, the ceiling the eager outer
  * step (K = 4M + 1) is compared with.  K in {1, 2, 4, 5, 8, 9, 16, 17, 33}; n a multiple of 4;
- * base 16-byte aligned, stride a multiple of 4.
+ * base 16-byte aligned, stride a multiple of 4.  launch: as above, NULL = automatic.
  */
-int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stride, void* stream);
+int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stride, void* stream,
+                          const diloco_launch* launch);
 
 /*
- * Launch tuning for measurements.  Keys:
- *   "block"        threads per workgroup of the streaming kernels: 64..512, power of two; 0 (the
- *                  default) lets each launch choose: one-wavefront workgroups, throttled as below.
- *   "xcd_remap"    0/1: give each of the 8 XCDs a contiguous slice of the index space.
- *   "wg_per_cu"    at most this many workgroups of a streaming kernel resident on a compute unit
- *                  (1..32; enforced with dynamic LDS the kernel never touches); 0: no cap; -1 (the
- *                  default): with "block" 0 the launch picks the cap that puts about 32-64 KB of
- *                  loads in flight per compute unit, with an explicit "block" there is no cap.
- *   "generic_path" 0 = the eager entry points choose their kernel (register-resident for M <= 8,
- *                  beyond that the first 40 replicas staged in LDS and the rest read twice);
- *                  1 = for every M, up to 80 replicas staged; 2 = for every M, none staged.
- * Results do not depend on any of them.
- * Returns DILOCO_OK or DILOCO_ERR_HYPER for an unknown key / value.  Not thread safe.
+ * The launch shape that calls WITHOUT an explicit shape use on the calling thread (test aid): the
+ * fields of diloco_launch by name, "block", "xcd_remap", "wg_per_cu", "generic_path", with the
+ * same ranges.  The setting is per thread (thread-local storage): a thread never sees another
+ * thread's values, and a new thread starts from the automatic choice.  Results do not depend
+ * on any of them.  Returns DILOCO_OK, or DILOCO_ERR_HYPER for an unknown key / value
+ * (diloco_tune_get: -1 for an unknown key; wg_per_cu may itself read -1).
  */
 int diloco_tune(const char* key, int value);
 int diloco_tune_get(const char* key);

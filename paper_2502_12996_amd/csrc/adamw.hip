@@ -223,24 +223,27 @@ static AdamScalars make_adam(double lr, double b1, double b2, double eps, double
 
 template <typename PT, typename GT>
 static int launch_adamw(void* theta, void* m1, void* m2, const void* grad, int M, int64_t n,
-                        int64_t stride, const AdamScalars& sc, bool vec_ok, hipStream_t st) {
+                        int64_t stride, const AdamScalars& sc, bool vec_ok, hipStream_t st, const Tuning& t) {
     // a wavefront of the vector kernel loads theta, m1, m2 and the gradient of 256 parameters
-    const Shape shape = launch_shape((int64_t)64 * 4 * (3 * sizeof(PT) + sizeof(GT)), kInFlightTarget);
+    const Shape shape = launch_shape(t, (int64_t)64 * 4 * (3 * sizeof(PT) + sizeof(GT)), kInFlightTarget);
     const int block = shape.block;
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(threads, block);
+    Grid g = make_grid(t, threads, block);
     if (vec_ok) {
         if (!grant_lds(&adamw_vec_kernel<PT, GT>, shape.lds)) return DILOCO_ERR_LAUNCH;
-        hipLaunchKernelGGL((adamw_vec_kernel<PT, GT>), dim3(g.blocks, M), dim3(block), shape.lds, st,
-                           static_cast<PT*>(theta), static_cast<PT*>(m1), static_cast<PT*>(m2),
-                           static_cast<const GT*>(grad), n, stride, sc, g.per_xcd);
-    } else
-        hipLaunchKernelGGL((adamw_scalar_kernel<PT, GT>), dim3(g.blocks, M), dim3(block), 0, st,
-                           static_cast<PT*>(theta), static_cast<PT*>(m1), static_cast<PT*>(m2),
-                           static_cast<const GT*>(grad), n, stride, sc, g.per_xcd);
-    return launch_status();
+        return launch(adamw_vec_kernel<PT, GT>, dim3(g.blocks, M), dim3(block), shape.lds, st,
+                      static_cast<PT*>(theta), static_cast<PT*>(m1), static_cast<PT*>(m2),
+                      static_cast<const GT*>(grad), n, stride, sc, g.per_xcd);
+    }
+    return launch(adamw_scalar_kernel<PT, GT>, dim3(g.blocks, M), dim3(block), 0, st, static_cast<PT*>(theta),
+                  static_cast<PT*>(m1), static_cast<PT*>(m2), static_cast<const GT*>(grad), n, stride, sc,
+                  g.per_xcd);
 }
+
+static int inner_adamw_impl(void* theta, void* m1, void* m2, const void* grad, int M, int64_t n, int64_t stride,
+                            int param_dtype, int grad_dtype, double lr, double beta1, double beta2, double eps,
+                            double weight_decay, int64_t step, void* stream, const Tuning& t);
 
 }  // namespace diloco
 
@@ -250,6 +253,25 @@ extern "C" int diloco_inner_adamw(void* theta, void* m1, void* m2, const void* g
                                   int64_t n, int64_t stride, diloco_dtype param_dtype,
                                   diloco_dtype grad_dtype, double lr, double beta1, double beta2,
                                   double eps, double weight_decay, int64_t step, void* stream) {
+    return inner_adamw_impl(theta, m1, m2, grad, M, n, stride, param_dtype, grad_dtype, lr, beta1, beta2, eps,
+                            weight_decay, step, stream, tuning());
+}
+
+extern "C" int diloco_inner_adamw_shaped(void* theta, void* m1, void* m2, const void* grad, int M,
+                                         int64_t n, int64_t stride, diloco_dtype param_dtype,
+                                         diloco_dtype grad_dtype, double lr, double beta1, double beta2,
+                                         double eps, double weight_decay, int64_t step, void* stream,
+                                         const diloco_launch* launch_arg) {
+    Tuning t;
+    if (!resolve_launch(launch_arg, t)) return DILOCO_ERR_HYPER;
+    return inner_adamw_impl(theta, m1, m2, grad, M, n, stride, param_dtype, grad_dtype, lr, beta1, beta2, eps,
+                            weight_decay, step, stream, t);
+}
+
+static int diloco::inner_adamw_impl(void* theta, void* m1, void* m2, const void* grad, int M, int64_t n,
+                                    int64_t stride, int param_dtype, int grad_dtype, double lr, double beta1,
+                                    double beta2, double eps, double weight_decay, int64_t step, void* stream,
+                                    const Tuning& t) {
     if (!theta || !m1 || !m2 || !grad) return DILOCO_ERR_NULL;
     if (!valid_dtype(param_dtype) || !valid_dtype(grad_dtype)) return DILOCO_ERR_DTYPE;
     if (int e = check_shape(M, n, stride)) return e;
@@ -268,12 +290,12 @@ extern "C" int diloco_inner_adamw(void* theta, void* m1, void* m2, const void* g
     const AdamScalars sc = make_adam(lr, beta1, beta2, eps, weight_decay, step);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (param_dtype == DILOCO_F32 && grad_dtype == DILOCO_F32)
-        return launch_adamw<float, float>(theta, m1, m2, grad, M, n, stride, sc, vec_ok, st);
+        return launch_adamw<float, float>(theta, m1, m2, grad, M, n, stride, sc, vec_ok, st, t);
     if (param_dtype == DILOCO_F32)
-        return launch_adamw<float, __bf16>(theta, m1, m2, grad, M, n, stride, sc, vec_ok, st);
+        return launch_adamw<float, __bf16>(theta, m1, m2, grad, M, n, stride, sc, vec_ok, st, t);
     if (grad_dtype == DILOCO_F32)
-        return launch_adamw<__bf16, float>(theta, m1, m2, grad, M, n, stride, sc, vec_ok, st);
-    return launch_adamw<__bf16, __bf16>(theta, m1, m2, grad, M, n, stride, sc, vec_ok, st);
+        return launch_adamw<__bf16, float>(theta, m1, m2, grad, M, n, stride, sc, vec_ok, st, t);
+    return launch_adamw<__bf16, __bf16>(theta, m1, m2, grad, M, n, stride, sc, vec_ok, st, t);
 }
 
 extern "C" int diloco_sim_quadratic_inner(float* theta, float* m1, float* m2, int M, int64_t n,
@@ -302,16 +324,15 @@ extern "C" int diloco_sim_quadratic_inner(float* theta, float* m1, float* m2, in
     // the kernel walks the replicas one at a time: a wavefront has h, theta* and one replica's
     // theta, m1, m2 in flight, 16 B a lane each; the noise generator keeps the ALU busy for long, so
     // more wavefronts than for the plain sweeps pay (measured best at M = 4: 12 workgroups per CU)
-    const Shape shape = launch_shape((int64_t)64 * 16 * 5, 64 * 1024);
+    const Tuning& t = tuning();
+    const Shape shape = launch_shape(t, (int64_t)64 * 16 * 5, 64 * 1024);
     const int block = shape.block;
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(threads, block);
+    Grid g = make_grid(t, threads, block);
     if (!grant_lds(&quadratic_inner_kernel, shape.lds)) return DILOCO_ERR_LAUNCH;
-    hipLaunchKernelGGL(quadratic_inner_kernel, dim3(g.blocks), dim3(block), shape.lds,
-                       static_cast<hipStream_t>(stream), theta, m1, m2, h, theta_star, M, n, stride,
-                       (float)noise_std, k0, index_base, sc, g.per_xcd);
-    return launch_status();
+    return launch(quadratic_inner_kernel, dim3(g.blocks), dim3(block), shape.lds, static_cast<hipStream_t>(stream),
+                  theta, m1, m2, h, theta_star, M, n, stride, (float)noise_std, k0, index_base, sc, g.per_xcd);
 }
 
 extern "C" int diloco_sim_quadratic_phase(float* theta, float* m1, float* m2, int M, int64_t n,
@@ -344,12 +365,12 @@ extern "C" int diloco_sim_quadratic_phase(float* theta, float* m1, float* m2, in
         ps.inv_bc2[s] = one.inv_bc2;
     }
     // bound by the vector ALU: full occupancy, no throttle
-    const int block = plain_block();
+    const Tuning& t = tuning();
+    const int block = plain_block(t);
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(threads, block);
-    hipLaunchKernelGGL(quadratic_phase_kernel, dim3(g.blocks, M), dim3(block), 0,
-                       static_cast<hipStream_t>(stream), theta, m1, m2, h, theta_star, n, stride,
-                       (float)noise_std, seed, step_first, steps, index_base, sc, ps, g.per_xcd);
-    return launch_status();
+    Grid g = make_grid(t, threads, block);
+    return launch(quadratic_phase_kernel, dim3(g.blocks, M), dim3(block), 0, static_cast<hipStream_t>(stream), theta,
+                  m1, m2, h, theta_star, n, stride, (float)noise_std, seed, step_first, steps, index_base, sc, ps,
+                  g.per_xcd);
 }

@@ -5,8 +5,11 @@
 #include <stdint.h>
 
 #include <cmath>
+#include <tuple>
+#include <utility>
 
 #include "diloco.h"
+#include "diloco_sim.h"
 
 namespace diloco {
 
@@ -82,7 +85,27 @@ struct Tuning {
                            // 1 for every M, staging 80; 2 for every M, staging none
     int wg_per_cu = -1;    // most workgroups of a streaming kernel resident on a CU; 0: no cap, -1: chosen per launch
 };
+// The calling thread's launch shape (diloco_tune): what an entry point without an explicit shape uses.
 Tuning& tuning();
+// Range checks shared by diloco_tune and the explicit-shape entry points.
+inline bool valid_block(int v) { return v == 0 || (v >= 64 && v <= kMaxBlock && (v & (v - 1)) == 0); }
+inline bool valid_tuning(const Tuning& t) {
+    return valid_block(t.block) && (t.xcd_remap == 0 || t.xcd_remap == 1) && t.generic_path >= 0 &&
+           t.generic_path <= 2 && t.wg_per_cu >= -1 && t.wg_per_cu <= 32;
+}
+// The shape of a *_shaped call: the caller's struct, or the thread's shape for NULL.  false if a
+// field is out of range.
+inline bool resolve_launch(const diloco_launch* l, Tuning& out) {
+    if (!l) {
+        out = tuning();
+        return true;
+    }
+    out.block = l->block;
+    out.xcd_remap = l->xcd_remap;
+    out.wg_per_cu = l->wg_per_cu;
+    out.generic_path = l->generic_path;
+    return valid_tuning(out);
+}
 
 constexpr int kLdsPerCu = 160 * 1024;  // gfx950
 
@@ -110,8 +133,7 @@ inline size_t cap_lds_bytes(int cap) {
     const size_t b = (size_t)kLdsPerCu / (size_t)(cap + 1) + 1;
     return (b + 255) & ~(size_t)255;
 }
-inline Shape launch_shape(int64_t wave_load_bytes, int64_t target_bytes) {
-    const Tuning& t = tuning();
+inline Shape launch_shape(const Tuning& t, int64_t wave_load_bytes, int64_t target_bytes) {
     Shape s{t.block ? t.block : 64, 0};
     int cap = t.wg_per_cu;
     if (cap < 0) {
@@ -126,7 +148,7 @@ inline Shape launch_shape(int64_t wave_load_bytes, int64_t target_bytes) {
     return s;
 }
 // Workgroup size of the kernels that take no throttle.
-inline int plain_block() { return tuning().block ? tuning().block : 256; }
+inline int plain_block(const Tuning& t) { return t.block ? t.block : 256; }
 // More than 48 KB of dynamic LDS has to be granted per kernel, once: the largest size granted so
 // far is remembered per kernel and device, so that a launch in steady state sets no attribute.
 // false if the runtime refuses.
@@ -179,10 +201,10 @@ struct Grid {
     unsigned blocks;
     int64_t per_xcd;
 };
-inline Grid make_grid(int64_t threads, int block) {
+inline Grid make_grid(const Tuning& t, int64_t threads, int block) {
     int64_t nb = (threads + block - 1) / block;
     Grid g;
-    if (tuning().xcd_remap && nb >= 4 * kXcds) {
+    if (t.xcd_remap && nb >= 4 * kXcds) {
         g.per_xcd = (nb + kXcds - 1) / kXcds;
         g.blocks = (unsigned)(g.per_xcd * kXcds);
     } else {
@@ -196,8 +218,22 @@ inline bool grid_fits(int64_t threads, int block) {
     return (threads + block - 1) / block + kXcds < ((int64_t)1 << 31);
 }
 
-inline int launch_status() {
-    return hipGetLastError() == hipSuccess ? DILOCO_OK : DILOCO_ERR_LAUNCH;
+// Enqueues one kernel and reports the status of THIS launch: the thread's last-error slot is
+// neither read nor cleared, so an unrelated earlier error is neither reported nor swallowed.
+template <typename... KArgs, typename... Args, size_t... I>
+inline int launch_impl(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                       std::index_sequence<I...>, Args&&... args) {
+    std::tuple<KArgs...> vals(static_cast<KArgs>(std::forward<Args>(args))...);
+    void* ptrs[] = {static_cast<void*>(&std::get<I>(vals))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds, st) == hipSuccess
+               ? DILOCO_OK
+               : DILOCO_ERR_LAUNCH;
+}
+template <typename... KArgs, typename... Args>
+inline int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st, Args&&... args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count does not match the kernel's");
+    return launch_impl(kernel, grid, block, lds, st, std::index_sequence_for<KArgs...>{},
+                       std::forward<Args>(args)...);
 }
 
 }  // namespace diloco

@@ -71,7 +71,6 @@ __device__ __forceinline__ f4 sent(f4 d, const OuterScalars& sc) {
 
 enum { MODE_RECORD = 0, MODE_EAGER = 1, MODE_DELAYED = 2 };
 
-constexpr int kMaxRegisterReplicas = 8;  // register-resident eager kernels exist for M = 1..8
 constexpr int kMinStagedWaves = 2;     // replicas are staged in LDS only while this many wavefronts fit a CU
 constexpr int kTileShift = 13;  // DILOCO_STATE_TILE = 8192 elements
 constexpr int64_t kTile = (int64_t)1 << kTileShift;
@@ -265,39 +264,51 @@ constexpr int kGroup = 8;
 
 // First pass over one group: Delta_m = a_m - theta_m into the running sum; with LDS staging the
 // values the second pass needs are parked (a_m, or theta_m when only recording, and Delta_m).
-template <typename TT, int MODE, typename SV, bool FULL, bool STAGE>
+// NOMEAN (eager step without a stored mean): the previous local outer gradients are read here as
+// well, summed into t0..t3 in replica order, and parked with the others (a third slot).
+template <typename TT, int MODE, typename SV, bool FULL, bool STAGE, bool NOMEAN>
 __device__ __forceinline__ void group_reduce(const TT* __restrict__ theta, const SV& sv, int m0, int cnt,
                                              int64_t i, int64_t stride, const OuterScalars& sc, f4* stage,
-                                             int tid, double& s0, double& s1, double& s2, double& s3) {
-    f4 a[kGroup], th[kGroup];
+                                             int tid, double (&s)[4], double (&t)[4]) {
+    constexpr int kSlots = NOMEAN ? 3 : 2;
+    f4 a[kGroup], th[kGroup], p[kGroup];
 #pragma unroll
     for (int j = 0; j < kGroup; ++j)
         if (FULL || j < cnt) {
             a[j] = load4(sv.a(m0 + j, i));
             th[j] = load4(theta + (m0 + j) * stride + i);
+            if (NOMEAN) p[j] = load4(sv.p(m0 + j, i));
         }
 #pragma unroll
     for (int j = 0; j < kGroup; ++j)
         if (FULL || j < cnt) {
             const f4 d = a[j] - th[j];
             const f4 q = sent(d, sc);
-            s0 += (double)q.x;
-            s1 += (double)q.y;
-            s2 += (double)q.z;
-            s3 += (double)q.w;
+            s[0] += (double)q.x;
+            s[1] += (double)q.y;
+            s[2] += (double)q.z;
+            s[3] += (double)q.w;
+            if (NOMEAN) {
+                t[0] += (double)p[j].x;
+                t[1] += (double)p[j].y;
+                t[2] += (double)p[j].z;
+                t[3] += (double)p[j].w;
+            }
             if (STAGE) {
-                stage[(2 * (m0 + j)) * 64 + tid] = (MODE == MODE_RECORD) ? th[j] : a[j];
-                stage[(2 * (m0 + j) + 1) * 64 + tid] = d;
+                stage[(kSlots * (m0 + j)) * 64 + tid] = (MODE == MODE_RECORD) ? th[j] : a[j];
+                stage[(kSlots * (m0 + j) + 1) * 64 + tid] = d;
+                if (NOMEAN) stage[(kSlots * (m0 + j) + 2) * 64 + tid] = p[j];
             }
         }
 }
 
-// Second pass over one group.  STAGE: a_m (theta_m) and Delta_m come back from LDS; otherwise
-// theta_m and a_m are read again.
-template <typename TT, int MODE, typename SV, bool FULL, bool STAGE>
+// Second pass over one group.  STAGE: a_m (theta_m) and Delta_m (and, NOMEAN, the previous local
+// outer gradient) come back from LDS; otherwise they are read again.
+template <typename TT, int MODE, typename SV, bool FULL, bool STAGE, bool NOMEAN>
 __device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& sv, int m0, int cnt, int64_t i,
                                              int64_t stride, const OuterScalars& sc, const f4* stage, int tid,
                                              f4 Dold) {
+    constexpr int kSlots = NOMEAN ? 3 : 2;
     f4 a[kGroup], d[kGroup], u[kGroup], p[kGroup];
 #pragma unroll
     for (int j = 0; j < kGroup; ++j)
@@ -307,14 +318,15 @@ __device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& s
                 d[j] = load4(theta + (m0 + j) * stride + i);  // theta for now
             }
             if (MODE != MODE_RECORD) u[j] = load4(sv.u(m0 + j, i));
-            if (MODE == MODE_EAGER) p[j] = load4(sv.p(m0 + j, i));
+            if (MODE == MODE_EAGER && !(STAGE && NOMEAN)) p[j] = load4(sv.p(m0 + j, i));
         }
 #pragma unroll
     for (int j = 0; j < kGroup; ++j)
         if (FULL || j < cnt) {
             if (STAGE) {
-                a[j] = stage[(2 * (m0 + j)) * 64 + tid];  // theta_m when only recording
-                d[j] = stage[(2 * (m0 + j) + 1) * 64 + tid];
+                a[j] = stage[(kSlots * (m0 + j)) * 64 + tid];  // theta_m when only recording
+                d[j] = stage[(kSlots * (m0 + j) + 1) * 64 + tid];
+                if (NOMEAN) p[j] = stage[(kSlots * (m0 + j) + 2) * 64 + tid];
             } else {
                 const f4 th = d[j];
                 d[j] = a[j] - th;
@@ -343,14 +355,18 @@ __device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& s
 }
 
 // The first `staged` replicas (a multiple of kGroup, or all M) keep a_m and Delta_m in LDS between
-// the passes (32 bytes per lane and replica; a lane only reads back what it wrote itself, so no
-// barrier); for the others the second pass re-reads theta_m and a_m (2 of their 8 accesses per
-// index happen twice).  One wavefront per workgroup.
-template <typename TT, int MODE, typename SV>
+// the passes (32 bytes per lane and replica, 48 with NOMEAN; a lane only reads back what it wrote
+// itself, so no barrier); for the others the second pass re-reads theta_m and a_m (2 of their 8
+// accesses per index happen twice; with NOMEAN the previous local outer gradient as well).  One
+// wavefront per workgroup.  NOMEAN is the eager step without a stored mean (MODE_EAGER only): the
+// previous mean is the fp64 sum of the previous locals in replica order, rounded once, and the
+// mean stream is neither read nor written (recording without a stored mean only skips the store).
+template <typename TT, int MODE, typename SV, bool NOMEAN>
 __global__ __launch_bounds__(64) void outer_eager_grouped_kernel(TT* __restrict__ theta, SV sv, int M, int staged,
                                                                  int64_t n, int64_t stride, OuterScalars sc,
                                                                  int64_t per_xcd) {
-    extern __shared__ f4 stage[];  // [staged][2][64]
+    static_assert(!NOMEAN || MODE == MODE_EAGER, "only the eager combination forms the previous mean itself");
+    extern __shared__ f4 stage[];  // [staged][2 or 3][64]
     const int64_t v = logical_block(per_xcd) * 64 + threadIdx.x;
     const int64_t nvec = n >> 2;
     if (v >= nvec) {
@@ -359,37 +375,41 @@ __global__ __launch_bounds__(64) void outer_eager_grouped_kernel(TT* __restrict_
     }
     const int64_t i = v << 2;
     const int tid = threadIdx.x;
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    double s[4] = {0.0, 0.0, 0.0, 0.0}, t[4] = {0.0, 0.0, 0.0, 0.0};
     int m0 = 0;
     for (; m0 + kGroup <= M; m0 += kGroup) {
         if (m0 < staged)
-            group_reduce<TT, MODE, SV, true, true>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, s0, s1, s2, s3);
+            group_reduce<TT, MODE, SV, true, true, NOMEAN>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, s, t);
         else
-            group_reduce<TT, MODE, SV, true, false>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, s0, s1, s2, s3);
+            group_reduce<TT, MODE, SV, true, false, NOMEAN>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, s, t);
     }
     if (m0 < M) {
         if (m0 < staged)
-            group_reduce<TT, MODE, SV, false, true>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, s0, s1, s2, s3);
+            group_reduce<TT, MODE, SV, false, true, NOMEAN>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, s, t);
         else
-            group_reduce<TT, MODE, SV, false, false>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, s0, s1, s2, s3);
+            group_reduce<TT, MODE, SV, false, false, NOMEAN>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, s, t);
     }
-    f4 dbar = {(float)(s0 * sc.inv_M_d), (float)(s1 * sc.inv_M_d), (float)(s2 * sc.inv_M_d),
-               (float)(s3 * sc.inv_M_d)};
+    f4 dbar = {(float)(s[0] * sc.inv_M_d), (float)(s[1] * sc.inv_M_d), (float)(s[2] * sc.inv_M_d),
+               (float)(s[3] * sc.inv_M_d)};
     f4 Dold = {0.f, 0.f, 0.f, 0.f};
-    if (MODE != MODE_RECORD) Dold = load4(sv.d(i));
+    if (NOMEAN)
+        Dold = f4{(float)(t[0] * sc.inv_M_d), (float)(t[1] * sc.inv_M_d), (float)(t[2] * sc.inv_M_d),
+                  (float)(t[3] * sc.inv_M_d)};
+    else if (MODE != MODE_RECORD)
+        Dold = load4(sv.d(i));
     for (m0 = 0; m0 + kGroup <= M; m0 += kGroup) {
         if (m0 < staged)
-            group_update<TT, MODE, SV, true, true>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
+            group_update<TT, MODE, SV, true, true, NOMEAN>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
         else
-            group_update<TT, MODE, SV, true, false>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
+            group_update<TT, MODE, SV, true, false, NOMEAN>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
     }
     if (m0 < M) {
         if (m0 < staged)
-            group_update<TT, MODE, SV, false, true>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
+            group_update<TT, MODE, SV, false, true, NOMEAN>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
         else
-            group_update<TT, MODE, SV, false, false>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
+            group_update<TT, MODE, SV, false, false, NOMEAN>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
     }
-    store4(sv.d(i), dbar);
+    if (!sc.no_mean) store4(sv.d(i), dbar);
 }
 
 // ------------------------------------------------------------------ standard DiLoCo
@@ -594,30 +614,28 @@ static OuterScalars make_scalars(int M, double lr, double mu, int nesterov) {
 
 template <typename TT, int MODE, typename SV>
 static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, const OuterScalars& sc,
-                        bool vec_ok, hipStream_t st) {
+                        bool vec_ok, hipStream_t st, const Tuning& t) {
     // a wavefront of the vector kernels loads theta_m, a_m, u_m, P_m of every replica and D: 16 B a lane each
-    const Shape shape = launch_shape((int64_t)64 * ((3 * M + 1) * 16 + M * 4 * (int64_t)sizeof(TT)), kInFlightTarget);
+    const Shape shape =
+        launch_shape(t, (int64_t)64 * ((3 * M + 1) * 16 + M * 4 * (int64_t)sizeof(TT)), kInFlightTarget);
     const int block = shape.block;
     if (!vec_ok) {
         if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
-        Grid g = make_grid(n, block);
-        hipLaunchKernelGGL((outer_eager_scalar_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(block), 0, st, theta,
-                           sv, M, n, stride, sc, g.per_xcd);
-        return launch_status();
+        Grid g = make_grid(t, n, block);
+        return launch(outer_eager_scalar_kernel<TT, MODE, SV>, dim3(g.blocks), dim3(block), 0, st, theta, sv, M, n,
+                      stride, sc, g.per_xcd);
     }
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, 64)) return DILOCO_ERR_SHAPE;
-#define DILOCO_REG_CASE(MM)                                                                               \
-    case MM: {                                                                                            \
-        Grid g = make_grid(threads, block);                                                               \
-        if (!grant_lds(&outer_eager_reg_kernel<MM, TT, MODE, SV>, shape.lds)) return DILOCO_ERR_LAUNCH;   \
-        hipLaunchKernelGGL((outer_eager_reg_kernel<MM, TT, MODE, SV>), dim3(g.blocks), dim3(block),       \
-                           shape.lds, st, theta, sv, n, stride, sc, g.per_xcd);                           \
-        return launch_status();                                                                           \
+#define DILOCO_REG_CASE(MM)                                                                             \
+    case MM: {                                                                                          \
+        Grid g = make_grid(t, threads, block);                                                          \
+        if (!grant_lds(&outer_eager_reg_kernel<MM, TT, MODE, SV>, shape.lds)) return DILOCO_ERR_LAUNCH; \
+        return launch(outer_eager_reg_kernel<MM, TT, MODE, SV>, dim3(g.blocks), dim3(block), shape.lds, st, theta,  \
+                      sv, n, stride, sc, g.per_xcd);                                                    \
     }
-    // a forced generic path also replaces the register kernels, unless the call does without the
-    // stored mean, which only they know how to do
-    switch ((tuning().generic_path && !sc.no_mean) ? 0 : M) {
+    // a forced generic path also replaces the register kernels
+    switch (t.generic_path ? 0 : M) {
         DILOCO_REG_CASE(1)
         DILOCO_REG_CASE(2)
         DILOCO_REG_CASE(3)
@@ -630,62 +648,81 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
     }
 #undef DILOCO_REG_CASE
     // Other M: the grouped kernel, one wavefront per workgroup.  It stages as many replicas in LDS
-    // (2 KB each per workgroup) as leave room for kMinStagedWaves workgroups on a CU's 160 KB: all
-    // of them up to M = 40, the first 40 beyond; the rest are read twice.  generic_path 1 stages
-    // all that one workgroup per CU can hold (80), 2 stages none.  The kernel's 256 VGPRs and the
-    // staging already keep it to 4 workgroups per CU or fewer; left to itself a launch that stages
-    // nothing is capped at 2.  Measured, of algorithmic bytes: 6.2-6.6 TB/s fully staged (M <= 40),
-    // 6.2 / 5.8 / 5.6 at M = 48 / 64 / 80, 5.3-5.8 unstaged.  A cap may ask for more LDS than the
-    // staging needs, never less.
-    const Tuning& t = tuning();
-    const int room = t.generic_path == 2 ? 0 : kLdsPerCu / (64 * 32) / (t.generic_path == 1 ? 1 : kMinStagedWaves);
+    // (2 KB each per workgroup, 3 KB when the previous mean is formed from the previous locals) as
+    // leave room for kMinStagedWaves workgroups on a CU's 160 KB: all of them up to M = 40 (26), the
+    // first 40 (24) beyond; the rest are read twice.  generic_path 1 stages all that one workgroup
+    // per CU can hold (80 / 53), 2 stages none.  The kernel's 256 VGPRs and the staging already keep
+    // it to 4 workgroups per CU or fewer; left to itself a launch that stages nothing is capped at 2.
+    // Measured, of algorithmic bytes: 6.2-6.6 TB/s fully staged (M <= 40), 6.2 / 5.8 / 5.6 at
+    // M = 48 / 64 / 80, 5.3-5.8 unstaged.  A cap may ask for more LDS than the staging needs, never less.
+    constexpr bool kNoMeanKernel = MODE == MODE_EAGER;
+    const bool nomean = kNoMeanKernel && sc.no_mean;
+    const int per_replica = 64 * 16 * (nomean ? 3 : 2);
+    const int room = t.generic_path == 2 ? 0 : kLdsPerCu / per_replica / (t.generic_path == 1 ? 1 : kMinStagedWaves);
     const int staged = M <= room ? M : room / kGroup * kGroup;
-    const int64_t need = (int64_t)64 * 32 * staged;
+    const int64_t need = (int64_t)per_replica * staged;
     const int cap = t.wg_per_cu >= 0 ? t.wg_per_cu : (staged ? 0 : 2);
     const int64_t cap_lds = (int64_t)cap_lds_bytes(cap);
     const size_t lds = (size_t)(need > cap_lds ? need : cap_lds);
-    if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV>, lds)) return DILOCO_ERR_LAUNCH;
-    Grid g = make_grid(threads, 64);
-    hipLaunchKernelGGL((outer_eager_grouped_kernel<TT, MODE, SV>), dim3(g.blocks), dim3(64), lds, st, theta, sv,
-                       M, staged, n, stride, sc, g.per_xcd);
-    return launch_status();
+    Grid g = make_grid(t, threads, 64);
+    if (nomean) {
+        // only instantiated for the eager mode (the others never form the previous mean)
+        auto kernel = outer_eager_grouped_kernel<TT, kNoMeanKernel ? MODE : MODE_EAGER, SV, true>;
+        if (!grant_lds(kernel, lds)) return DILOCO_ERR_LAUNCH;
+        return launch(kernel, dim3(g.blocks), dim3(64), lds, st, theta, sv, M, staged, n, stride, sc, g.per_xcd);
+    }
+    if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV, false>, lds)) return DILOCO_ERR_LAUNCH;
+    return launch(outer_eager_grouped_kernel<TT, MODE, SV, false>, dim3(g.blocks), dim3(64), lds, st, theta, sv, M,
+                  staged, n, stride, sc, g.per_xcd);
 }
 
 template <typename TT, typename SV>
 static int dispatch_eager(void* theta, SV sv, int M, int64_t n, int64_t stride, const OuterScalars& sc,
-                          bool vec_ok, int mode, hipStream_t st) {
+                          bool vec_ok, int mode, hipStream_t st, const Tuning& t) {
     TT* th = static_cast<TT*>(theta);
     switch (mode) {
-        case MODE_RECORD: return launch_eager<TT, MODE_RECORD, SV>(th, sv, M, n, stride, sc, vec_ok, st);
-        case MODE_EAGER: return launch_eager<TT, MODE_EAGER, SV>(th, sv, M, n, stride, sc, vec_ok, st);
-        default: return launch_eager<TT, MODE_DELAYED, SV>(th, sv, M, n, stride, sc, vec_ok, st);
+        case MODE_RECORD: return launch_eager<TT, MODE_RECORD, SV>(th, sv, M, n, stride, sc, vec_ok, st, t);
+        case MODE_EAGER: return launch_eager<TT, MODE_EAGER, SV>(th, sv, M, n, stride, sc, vec_ok, st, t);
+        default: return launch_eager<TT, MODE_DELAYED, SV>(th, sv, M, n, stride, sc, vec_ok, st, t);
     }
 }
 
 static int64_t packed_elems(int M, int64_t n) { return ((n + kTile - 1) >> kTileShift) * (3 * (int64_t)M + 1) * kTile; }
 
-static int mode_of(int variant, int apply_update) {
-    return !apply_update ? MODE_RECORD : (variant == DILOCO_EAGER ? MODE_EAGER : MODE_DELAYED);
+static int mode_of(int base, int apply_update) {
+    return !apply_update ? MODE_RECORD : (base == DILOCO_EAGER ? MODE_EAGER : MODE_DELAYED);
 }
 
-}  // namespace diloco
+// The `variant` argument of the eager entry points: base rule in the low byte, flag bits above.
+struct Variant {
+    int base;     // DILOCO_EAGER or DILOCO_DELAYED
+    int no_mean;  // DILOCO_STATE_NO_MEAN
+    OuterScalars wire;
+};
+static int parse_variant(int variant, Variant& v) {
+    v.no_mean = (variant & DILOCO_STATE_NO_MEAN) ? 1 : 0;
+    if (!parse_comm(variant & ~DILOCO_STATE_NO_MEAN & ~0xff, v.wire)) return DILOCO_ERR_DTYPE;
+    v.base = variant & 0xff;
+    if (v.base != DILOCO_EAGER && v.base != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
+    if (v.no_mean && v.base != DILOCO_EAGER) return DILOCO_ERR_DTYPE;
+    return DILOCO_OK;
+}
+static OuterScalars eager_scalars(int M, double lr, double mu, int nesterov, const Variant& v) {
+    OuterScalars sc = make_scalars(M, lr, mu, nesterov);
+    sc.comm = v.wire.comm, sc.q_mant = v.wire.q_mant, sc.q_emin = v.wire.q_emin, sc.q_bias = v.wire.q_bias;
+    sc.q_max = v.wire.q_max;
+    sc.no_mean = v.no_mean;
+    return sc;
+}
 
-using namespace diloco;
-
-extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
-                                  int64_t stride, float* anchor, float* vel, float* prev_local,
-                                  int64_t state_stride, float* prev_mean, double outer_lr,
-                                  double outer_momentum, int nesterov, diloco_variant variant,
-                                  int apply_update, void* stream) {
+static int outer_eager_impl(void* theta, int theta_dtype, int M, int64_t n, int64_t stride, float* anchor,
+                            float* vel, float* prev_local, int64_t state_stride, float* prev_mean,
+                            double outer_lr, double outer_momentum, int nesterov, int variant, int apply_update,
+                            void* stream, const Tuning& t) {
     if (!theta || !anchor || !vel || !prev_local || !prev_mean) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
-    OuterScalars comm;
-    const int no_mean = (variant & DILOCO_STATE_NO_MEAN) ? 1 : 0;
-    if (!parse_comm(variant & ~DILOCO_STATE_NO_MEAN, comm)) return DILOCO_ERR_DTYPE;
-    variant = static_cast<diloco_variant>(variant & 0xff);
-    if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
-    if (no_mean && variant != DILOCO_EAGER) return DILOCO_ERR_DTYPE;
-    if (no_mean && M > kMaxRegisterReplicas) return DILOCO_ERR_SHAPE;
+    Variant v;
+    if (int e = parse_variant(variant, v)) return e;
     if (int e = check_shape(M, n, stride)) return e;
     if (int e = check_shape(M, n, state_stride)) return e;
     if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
@@ -703,34 +740,21 @@ extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, 
     const bool vec_ok = aligned_to(theta, 4 * es) && aligned_to(anchor, 16) && aligned_to(vel, 16) &&
                         aligned_to(prev_local, 16) && aligned_to(prev_mean, 16) &&
                         (M == 1 || (stride % 4 == 0 && state_stride % 4 == 0));
-    OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
-    sc.comm = comm.comm, sc.q_mant = comm.q_mant, sc.q_emin = comm.q_emin, sc.q_bias = comm.q_bias, sc.q_max = comm.q_max;
-    sc.no_mean = no_mean;
+    const OuterScalars sc = eager_scalars(M, outer_lr, outer_momentum, nesterov, v);
     const RowState sv{anchor, vel, prev_local, prev_mean, state_stride};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (theta_dtype == DILOCO_F32)
-        return dispatch_eager<float, RowState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);
-    return dispatch_eager<__bf16, RowState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);
+    const int mode = mode_of(v.base, apply_update);
+    if (theta_dtype == DILOCO_F32) return dispatch_eager<float, RowState>(theta, sv, M, n, stride, sc, vec_ok, mode, st, t);
+    return dispatch_eager<__bf16, RowState>(theta, sv, M, n, stride, sc, vec_ok, mode, st, t);
 }
 
-extern "C" int64_t diloco_packed_state_elems(int M, int64_t n) {
-    if (M < 1 || M > DILOCO_MAX_REPLICAS || n < 0 || n > ((int64_t)1 << 40)) return -1;
-    return packed_elems(M, n);
-}
-
-extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
-                                         int64_t stride, float* state, double outer_lr,
-                                         double outer_momentum, int nesterov, diloco_variant variant,
-                                         int apply_update, void* stream) {
+static int outer_eager_packed_impl(void* theta, int theta_dtype, int M, int64_t n, int64_t stride, float* state,
+                                   double outer_lr, double outer_momentum, int nesterov, int variant,
+                                   int apply_update, void* stream, const Tuning& t) {
     if (!theta || !state) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
-    OuterScalars comm;
-    const int no_mean = (variant & DILOCO_STATE_NO_MEAN) ? 1 : 0;
-    if (!parse_comm(variant & ~DILOCO_STATE_NO_MEAN, comm)) return DILOCO_ERR_DTYPE;
-    variant = static_cast<diloco_variant>(variant & 0xff);
-    if (variant != DILOCO_EAGER && variant != DILOCO_DELAYED) return DILOCO_ERR_DTYPE;
-    if (no_mean && variant != DILOCO_EAGER) return DILOCO_ERR_DTYPE;
-    if (no_mean && M > kMaxRegisterReplicas) return DILOCO_ERR_SHAPE;
+    Variant v;
+    if (int e = parse_variant(variant, v)) return e;
     if (int e = check_shape(M, n, stride)) return e;
     if (n > ((int64_t)1 << 40)) return DILOCO_ERR_SHAPE;
     if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
@@ -740,14 +764,60 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
     if (int e = check_alias(r, 2)) return e;
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
-    OuterScalars sc = make_scalars(M, outer_lr, outer_momentum, nesterov);
-    sc.comm = comm.comm, sc.q_mant = comm.q_mant, sc.q_emin = comm.q_emin, sc.q_bias = comm.q_bias, sc.q_max = comm.q_max;
-    sc.no_mean = no_mean;
+    const OuterScalars sc = eager_scalars(M, outer_lr, outer_momentum, nesterov, v);
     const TiledState sv{state, (int64_t)M};
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const int mode = mode_of(v.base, apply_update);
     if (theta_dtype == DILOCO_F32)
-        return dispatch_eager<float, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);
-    return dispatch_eager<__bf16, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode_of(variant, apply_update), st);
+        return dispatch_eager<float, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode, st, t);
+    return dispatch_eager<__bf16, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode, st, t);
+}
+
+}  // namespace diloco
+
+using namespace diloco;
+
+extern "C" int diloco_outer_eager(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                  int64_t stride, float* anchor, float* vel, float* prev_local,
+                                  int64_t state_stride, float* prev_mean, double outer_lr,
+                                  double outer_momentum, int nesterov, int variant,
+                                  int apply_update, void* stream) {
+    return outer_eager_impl(theta, theta_dtype, M, n, stride, anchor, vel, prev_local, state_stride, prev_mean,
+                            outer_lr, outer_momentum, nesterov, variant, apply_update, stream, tuning());
+}
+
+extern "C" int diloco_outer_eager_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                         int64_t stride, float* anchor, float* vel, float* prev_local,
+                                         int64_t state_stride, float* prev_mean, double outer_lr,
+                                         double outer_momentum, int nesterov, int variant,
+                                         int apply_update, void* stream, const diloco_launch* launch) {
+    Tuning t;
+    if (!resolve_launch(launch, t)) return DILOCO_ERR_HYPER;
+    return outer_eager_impl(theta, theta_dtype, M, n, stride, anchor, vel, prev_local, state_stride, prev_mean,
+                            outer_lr, outer_momentum, nesterov, variant, apply_update, stream, t);
+}
+
+extern "C" int64_t diloco_packed_state_elems(int M, int64_t n) {
+    if (M < 1 || M > DILOCO_MAX_REPLICAS || n < 0 || n > ((int64_t)1 << 40)) return -1;
+    return packed_elems(M, n);
+}
+
+extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                         int64_t stride, float* state, double outer_lr,
+                                         double outer_momentum, int nesterov, int variant,
+                                         int apply_update, void* stream) {
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, outer_lr, outer_momentum, nesterov,
+                                   variant, apply_update, stream, tuning());
+}
+
+extern "C" int diloco_outer_eager_packed_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                                int64_t stride, float* state, double outer_lr,
+                                                double outer_momentum, int nesterov, int variant,
+                                                int apply_update, void* stream, const diloco_launch* launch) {
+    Tuning t;
+    if (!resolve_launch(launch, t)) return DILOCO_ERR_HYPER;
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, outer_lr, outer_momentum, nesterov,
+                                   variant, apply_update, stream, t);
 }
 
 // rows <-> tiled.  Any of anchor / vel / prev_local / prev_mean may be NULL (skipped).
@@ -766,25 +836,24 @@ static int repack(bool to_tiled, float* state, int M, int64_t n, float* anchor, 
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(anchor, 16) && aligned_to(vel, 16) && aligned_to(prev_local, 16) &&
                         aligned_to(prev_mean, 16) && (M == 1 || state_stride % 4 == 0);
-    const int block = plain_block();
+    const Tuning& t = tuning();
+    const int block = plain_block(t);
     const int64_t threads = vec_ok ? (n + 3) >> 2 : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(threads, block);
+    Grid g = make_grid(t, threads, block);
     dim3 grid(g.blocks, 3 * M + 1);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (to_tiled && vec_ok)
-        hipLaunchKernelGGL((repack_kernel<true, 4>), grid, dim3(block), 0, st, state, anchor, vel, prev_local,
-                           prev_mean, M, n, state_stride, g.per_xcd);
-    else if (to_tiled)
-        hipLaunchKernelGGL((repack_kernel<true, 1>), grid, dim3(block), 0, st, state, anchor, vel, prev_local,
-                           prev_mean, M, n, state_stride, g.per_xcd);
-    else if (vec_ok)
-        hipLaunchKernelGGL((repack_kernel<false, 4>), grid, dim3(block), 0, st, state, anchor, vel, prev_local,
-                           prev_mean, M, n, state_stride, g.per_xcd);
-    else
-        hipLaunchKernelGGL((repack_kernel<false, 1>), grid, dim3(block), 0, st, state, anchor, vel, prev_local,
-                           prev_mean, M, n, state_stride, g.per_xcd);
-    return launch_status();
+        return launch(repack_kernel<true, 4>, grid, dim3(block), 0, st, state, anchor, vel, prev_local, prev_mean, M,
+                      n, state_stride, g.per_xcd);
+    if (to_tiled)
+        return launch(repack_kernel<true, 1>, grid, dim3(block), 0, st, state, anchor, vel, prev_local, prev_mean, M,
+                      n, state_stride, g.per_xcd);
+    if (vec_ok)
+        return launch(repack_kernel<false, 4>, grid, dim3(block), 0, st, state, anchor, vel, prev_local, prev_mean, M,
+                      n, state_stride, g.per_xcd);
+    return launch(repack_kernel<false, 1>, grid, dim3(block), 0, st, state, anchor, vel, prev_local, prev_mean, M, n,
+                  state_stride, g.per_xcd);
 }
 
 extern "C" int diloco_pack_state(float* state, int M, int64_t n, const float* anchor, const float* vel,
@@ -802,30 +871,27 @@ extern "C" int diloco_unpack_state(const float* state, int M, int64_t n, float* 
 
 template <typename TT>
 static int launch_sync(TT* theta, float* anchor, float* vel, float* mean_out, int M, int64_t n,
-                       int64_t stride, const OuterScalars& sc, bool vec_ok, hipStream_t st) {
+                       int64_t stride, const OuterScalars& sc, bool vec_ok, hipStream_t st, const Tuning& t) {
     // a wavefront of the vector kernel has the anchor, the velocity and one group of theta_m in
     // flight; measured best (n = 2^26, fp32): 12 / 8 / 8 / 4 workgroups per CU at M = 1 / 2 / 4 / >= 8
     const int grp = M < kGroup ? M : kGroup;
-    const Shape shape = launch_shape((int64_t)64 * (2 * 16 + grp * 4 * (int64_t)sizeof(TT)), kInFlightTarget);
+    const Shape shape = launch_shape(t, (int64_t)64 * (2 * 16 + grp * 4 * (int64_t)sizeof(TT)), kInFlightTarget);
     const int block = shape.block;
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(threads, block);
+    Grid g = make_grid(t, threads, block);
     if (vec_ok) {
         if (!grant_lds(&outer_sync_vec_kernel<TT>, shape.lds)) return DILOCO_ERR_LAUNCH;
-        hipLaunchKernelGGL((outer_sync_vec_kernel<TT>), dim3(g.blocks), dim3(block), shape.lds, st, theta,
-                           anchor, vel, mean_out, M, n, stride, sc, g.per_xcd);
+        return launch(outer_sync_vec_kernel<TT>, dim3(g.blocks), dim3(block), shape.lds, st, theta, anchor, vel,
+                      mean_out, M, n, stride, sc, g.per_xcd);
     }
-    else
-        hipLaunchKernelGGL((outer_sync_scalar_kernel<TT>), dim3(g.blocks), dim3(block), 0, st, theta,
-                           anchor, vel, mean_out, M, n, stride, sc, g.per_xcd);
-    return launch_status();
+    return launch(outer_sync_scalar_kernel<TT>, dim3(g.blocks), dim3(block), 0, st, theta, anchor, vel, mean_out, M,
+                  n, stride, sc, g.per_xcd);
 }
 
-extern "C" int diloco_outer_sync_comm(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
-                                      int64_t stride, float* anchor, float* vel, float* mean_out,
-                                      double outer_lr, double outer_momentum, int nesterov, int comm,
-                                      void* stream) {
+static int outer_sync_impl(void* theta, int theta_dtype, int M, int64_t n, int64_t stride, float* anchor, float* vel,
+                           float* mean_out, double outer_lr, double outer_momentum, int nesterov, int comm,
+                           void* stream, const Tuning& t) {
     if (!theta || !anchor || !vel) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
     OuterScalars wire;
@@ -848,10 +914,26 @@ extern "C" int diloco_outer_sync_comm(void* theta, diloco_dtype theta_dtype, int
     sc.comm = wire.comm, sc.q_mant = wire.q_mant, sc.q_emin = wire.q_emin, sc.q_bias = wire.q_bias, sc.q_max = wire.q_max;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (theta_dtype == DILOCO_F32)
-        return launch_sync<float>(static_cast<float*>(theta), anchor, vel, mean_out, M, n, stride, sc,
-                                  vec_ok, st);
-    return launch_sync<__bf16>(static_cast<__bf16*>(theta), anchor, vel, mean_out, M, n, stride, sc,
-                               vec_ok, st);
+        return launch_sync<float>(static_cast<float*>(theta), anchor, vel, mean_out, M, n, stride, sc, vec_ok, st, t);
+    return launch_sync<__bf16>(static_cast<__bf16*>(theta), anchor, vel, mean_out, M, n, stride, sc, vec_ok, st, t);
+}
+
+extern "C" int diloco_outer_sync_comm(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                      int64_t stride, float* anchor, float* vel, float* mean_out,
+                                      double outer_lr, double outer_momentum, int nesterov, int comm,
+                                      void* stream) {
+    return outer_sync_impl(theta, theta_dtype, M, n, stride, anchor, vel, mean_out, outer_lr, outer_momentum,
+                           nesterov, comm, stream, tuning());
+}
+
+extern "C" int diloco_outer_sync_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                        int64_t stride, float* anchor, float* vel, float* mean_out,
+                                        double outer_lr, double outer_momentum, int nesterov, int comm,
+                                        void* stream, const diloco_launch* launch) {
+    Tuning t;
+    if (!resolve_launch(launch, t)) return DILOCO_ERR_HYPER;
+    return outer_sync_impl(theta, theta_dtype, M, n, stride, anchor, vel, mean_out, outer_lr, outer_momentum,
+                           nesterov, comm, stream, t);
 }
 
 extern "C" int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
@@ -864,17 +946,16 @@ extern "C" int diloco_outer_sync(void* theta, diloco_dtype theta_dtype, int M, i
 
 template <typename TT, typename AV>
 static int launch_reset(void* theta, AV av, int M, int64_t n, int64_t stride, bool vec_ok, hipStream_t st) {
-    const int block = plain_block();
+    const Tuning& t = tuning();
+    const int block = plain_block(t);
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(threads, block);
+    Grid g = make_grid(t, threads, block);
     if (vec_ok)
-        hipLaunchKernelGGL((reset_vec_kernel<TT, AV>), dim3(g.blocks, M), dim3(block), 0, st,
-                           static_cast<TT*>(theta), av, n, stride, g.per_xcd);
-    else
-        hipLaunchKernelGGL((reset_scalar_kernel<TT, AV>), dim3(g.blocks, M), dim3(block), 0, st,
-                           static_cast<TT*>(theta), av, n, stride, g.per_xcd);
-    return launch_status();
+        return launch(reset_vec_kernel<TT, AV>, dim3(g.blocks, M), dim3(block), 0, st, static_cast<TT*>(theta), av, n,
+                      stride, g.per_xcd);
+    return launch(reset_scalar_kernel<TT, AV>, dim3(g.blocks, M), dim3(block), 0, st, static_cast<TT*>(theta), av, n,
+                  stride, g.per_xcd);
 }
 
 extern "C" int diloco_reset(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,

@@ -10,7 +10,7 @@
 namespace diloco {
 
 Tuning& tuning() {
-    static Tuning t;
+    static thread_local Tuning t;  // per calling thread: no caller sees another thread's shape
     return t;
 }
 
@@ -101,15 +101,13 @@ __global__ __launch_bounds__(kMaxBlock) void stream_rmw_kernel(float* __restrict
 }
 
 template <int K>
-static int launch_rmw(float* base, int64_t stride, int64_t n, hipStream_t st) {
-    const Shape shape = launch_shape((int64_t)64 * 16 * K, kInFlightTarget);
+static int launch_rmw(float* base, int64_t stride, int64_t n, hipStream_t st, const Tuning& t) {
+    const Shape shape = launch_shape(t, (int64_t)64 * 16 * K, kInFlightTarget);
     const int64_t threads = n >> 2;
     if (!grid_fits(threads, shape.block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(threads, shape.block);
+    Grid g = make_grid(t, threads, shape.block);
     if (!grant_lds(&stream_rmw_kernel<K>, shape.lds)) return DILOCO_ERR_LAUNCH;
-    hipLaunchKernelGGL((stream_rmw_kernel<K>), dim3(g.blocks), dim3(shape.block), shape.lds, st, base, stride, n,
-                       g.per_xcd);
-    return launch_status();
+    return launch(stream_rmw_kernel<K>, dim3(g.blocks), dim3(shape.block), shape.lds, st, base, stride, n, g.per_xcd);
 }
 
 static int64_t loss_blocks(int64_t n) {
@@ -142,33 +140,36 @@ extern "C" int diloco_sim_quadratic_loss(const float* theta, int M, int64_t n, i
     if (int e = check_alias(r, 5)) return e;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t nb = loss_blocks(n);
-    hipLaunchKernelGGL(quadratic_loss_partial_kernel, dim3((unsigned)nb), dim3(kLossBlock), 0, st,
-                       theta, M, n, stride, h, theta_star, partials, 1.0 / M);
-    if (int e = launch_status()) return e;
-    hipLaunchKernelGGL(quadratic_loss_final_kernel, dim3(1), dim3(kLossBlock), 0, st, partials, nb,
-                       loss_out);
-    return launch_status();
+    if (int e = launch(quadratic_loss_partial_kernel, dim3((unsigned)nb), dim3(kLossBlock), 0, st, theta, M, n,
+                       stride, h, theta_star, partials, 1.0 / M))
+        return e;
+    return launch(quadratic_loss_final_kernel, dim3(1), dim3(kLossBlock), 0, st, partials, nb, loss_out);
 }
 
-extern "C" int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream) {
+extern "C" int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream,
+                                      const diloco_launch* launch_arg) {
+    Tuning t;
+    if (!resolve_launch(launch_arg, t)) return DILOCO_ERR_HYPER;
     if (!dst || !src) return DILOCO_ERR_NULL;
     if (n < 0 || n > ((int64_t)1 << 60)) return DILOCO_ERR_SHAPE;
     if (!aligned_to(dst, 16) || !aligned_to(src, 16)) return DILOCO_ERR_ALIGN;
     Range r[2] = {{dst, n * 4, true}, {src, n * 4, false}};
     if (int e = check_alias(r, 2)) return e;
     if (n == 0) return DILOCO_OK;
-    const Shape shape = launch_shape(64 * 16, kInFlightTarget);  // one load a lane: never throttled by itself
+    const Shape shape = launch_shape(t, 64 * 16, kInFlightTarget);  // one load a lane: never throttled by itself
     const int block = shape.block;
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
-    Grid g = make_grid(threads, block);
+    Grid g = make_grid(t, threads, block);
     if (!grant_lds(&stream_copy_kernel, shape.lds)) return DILOCO_ERR_LAUNCH;
-    hipLaunchKernelGGL(stream_copy_kernel, dim3(g.blocks), dim3(block), shape.lds,
-                       static_cast<hipStream_t>(stream), dst, src, n, g.per_xcd);
-    return launch_status();
+    return launch(stream_copy_kernel, dim3(g.blocks), dim3(block), shape.lds, static_cast<hipStream_t>(stream), dst,
+                  src, n, g.per_xcd);
 }
 
-extern "C" int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stride, void* stream) {
+extern "C" int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stride, void* stream,
+                                     const diloco_launch* launch_arg) {
+    Tuning t;
+    if (!resolve_launch(launch_arg, t)) return DILOCO_ERR_HYPER;
     if (!base) return DILOCO_ERR_NULL;
     if (n < 0 || (n & 3) || stride < n || K < 1) return DILOCO_ERR_SHAPE;
     if (stride > ((int64_t)1 << 50) / K) return DILOCO_ERR_SHAPE;
@@ -176,15 +177,15 @@ extern "C" int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stri
     if (n == 0) return DILOCO_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (K) {
-        case 1: return launch_rmw<1>(base, stride, n, st);
-        case 2: return launch_rmw<2>(base, stride, n, st);
-        case 4: return launch_rmw<4>(base, stride, n, st);
-        case 5: return launch_rmw<5>(base, stride, n, st);
-        case 8: return launch_rmw<8>(base, stride, n, st);
-        case 9: return launch_rmw<9>(base, stride, n, st);
-        case 16: return launch_rmw<16>(base, stride, n, st);
-        case 17: return launch_rmw<17>(base, stride, n, st);
-        case 33: return launch_rmw<33>(base, stride, n, st);
+        case 1: return launch_rmw<1>(base, stride, n, st, t);
+        case 2: return launch_rmw<2>(base, stride, n, st, t);
+        case 4: return launch_rmw<4>(base, stride, n, st, t);
+        case 5: return launch_rmw<5>(base, stride, n, st, t);
+        case 8: return launch_rmw<8>(base, stride, n, st, t);
+        case 9: return launch_rmw<9>(base, stride, n, st, t);
+        case 16: return launch_rmw<16>(base, stride, n, st, t);
+        case 17: return launch_rmw<17>(base, stride, n, st, t);
+        case 33: return launch_rmw<33>(base, stride, n, st, t);
         default: return DILOCO_ERR_SHAPE;
     }
 }
@@ -211,27 +212,20 @@ extern "C" int64_t diloco_stream_boundary_count(int64_t t, int64_t H, int F, int
 
 extern "C" int diloco_tune(const char* key, int value) {
     if (!key) return DILOCO_ERR_NULL;
-    if (!std::strcmp(key, "block")) {
-        if (value != 0 && (value < 64 || value > kMaxBlock || (value & (value - 1)))) return DILOCO_ERR_HYPER;
-        tuning().block = value;
-        return DILOCO_OK;
-    }
-    if (!std::strcmp(key, "xcd_remap")) {
-        if (value != 0 && value != 1) return DILOCO_ERR_HYPER;
-        tuning().xcd_remap = value;
-        return DILOCO_OK;
-    }
-    if (!std::strcmp(key, "generic_path")) {
-        if (value < 0 || value > 2) return DILOCO_ERR_HYPER;
-        tuning().generic_path = value;
-        return DILOCO_OK;
-    }
-    if (!std::strcmp(key, "wg_per_cu")) {
-        if (value < -1 || value > 32) return DILOCO_ERR_HYPER;
-        tuning().wg_per_cu = value;
-        return DILOCO_OK;
-    }
-    return DILOCO_ERR_HYPER;
+    Tuning t = tuning();
+    if (!std::strcmp(key, "block"))
+        t.block = value;
+    else if (!std::strcmp(key, "xcd_remap"))
+        t.xcd_remap = value;
+    else if (!std::strcmp(key, "generic_path"))
+        t.generic_path = value;
+    else if (!std::strcmp(key, "wg_per_cu"))
+        t.wg_per_cu = value;
+    else
+        return DILOCO_ERR_HYPER;
+    if (!valid_tuning(t)) return DILOCO_ERR_HYPER;
+    tuning() = t;
+    return DILOCO_OK;
 }
 
 extern "C" int diloco_tune_get(const char* key) {

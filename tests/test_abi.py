@@ -56,7 +56,7 @@ def eager(lib, theta=P[0], dt=0, M=2, n=64, stride=64, a=P[1], u=P[2], pl=P[3], 
 def test_variant_flags_are_validated_before_any_launch(lib):
     assert eager(lib, n=0, var=B.EAGER | B.STATE_NO_MEAN) == B.OK
     assert eager(lib, var=B.DELAYED | B.STATE_NO_MEAN) == B.ERR_DTYPE
-    assert eager(lib, M=9, stride=64, var=B.EAGER | B.STATE_NO_MEAN) == B.ERR_SHAPE
+    assert eager(lib, M=9, n=0, stride=64, var=B.EAGER | B.STATE_NO_MEAN) == B.OK   # any replica count
     assert eager(lib, var=B.EAGER | B.COMM_BF16 | B.COMM_EXMY(4, 3, 7)) == B.ERR_DTYPE
     assert eager(lib, var=B.EAGER | B.COMM_EXMY(0, 3, 7)) == B.ERR_DTYPE
     assert eager(lib, var=B.EAGER | B.COMM_EXMY(8, 7, 127)) == B.ERR_DTYPE     # below float32's normal range
@@ -69,7 +69,7 @@ def test_variant_flags_are_validated_before_any_launch(lib):
     assert sync(1) == B.ERR_DTYPE and sync(B.STATE_NO_MEAN) == B.ERR_DTYPE and sync(B.COMM_EXMY(9, 1, 0)) == B.ERR_DTYPE
 
     def rmw(K=4, n=64, stride=64, base=P[0]):
-        return lib.diloco_sim_stream_rmw(base, K, n, stride, None)
+        return lib.diloco_sim_stream_rmw(base, K, n, stride, None, None)
     assert rmw(n=0) == B.OK
     assert rmw(K=3) == B.ERR_SHAPE and rmw(n=62) == B.ERR_SHAPE and rmw(stride=32) == B.ERR_SHAPE
     assert rmw(base=None) == B.ERR_NULL and rmw(base=P[0] + 4) == B.ERR_ALIGN and rmw(stride=66) == B.ERR_ALIGN
@@ -214,30 +214,138 @@ def test_sim_validation_and_tuning(lib):
     assert lib.diloco_tune(b"wg_per_cu", 4) == B.OK and lib.diloco_tune_get(b"wg_per_cu") == 4
     assert lib.diloco_tune(b"wg_per_cu", -1) == B.OK
     assert lib.diloco_tune_get(b"nope") == -1
+    assert lib.diloco_tune(b"generic_path", 3) == B.ERR_HYPER and lib.diloco_tune(b"xcd_remap", 2) == B.ERR_HYPER
+
+
+def test_explicit_launch_shapes_are_validated(lib):
+    """The *_shaped entry points take the launch shape as an argument: NULL or a valid struct passes
+    on to the ordinary validation, a field out of range is refused before anything else."""
+    ok, bad = B.Launch(256, 1, 2, 0), [B.Launch(100, 0, -1, 0), B.Launch(0, 2, -1, 0), B.Launch(0, 0, 33, 0),
+                                        B.Launch(0, 0, -2, 0), B.Launch(64, 0, 0, 3), B.Launch(1024, 0, 0, 0)]
+    calls = {
+        "eager": lambda l, n=0: lib.diloco_outer_eager_shaped(P[0], 0, 2, n, 64, P[1], P[2], P[3], 64, P[4], 0.7, 0.9,
+                                                            1, 0, 1, None, l),
+        "packed": lambda l, n=0: lib.diloco_outer_eager_packed_shaped(P[0], 0, 2, n, 64, P[1], 0.7, 0.9, 1, 0, 1,
+                                                                    None, l),
+        "sync": lambda l, n=0: lib.diloco_outer_sync_shaped(P[0], 0, 2, n, 64, P[1], P[2], None, 0.7, 0.9, 1, 0,
+                                                          None, l),
+        "adamw": lambda l, n=0: lib.diloco_inner_adamw_shaped(P[0], P[1], P[2], P[3], 2, n, 64, 0, 0, 4e-4, 0.9, 0.95,
+                                                            1e-8, 0.1, 1, None, l),
+        "copy": lambda l, n=0: lib.diloco_sim_stream_copy(P[0], P[1], n, None, l),
+        "rmw": lambda l, n=0: lib.diloco_sim_stream_rmw(P[0], 4, n, 64, None, l),
+    }
+    for name, f in calls.items():
+        assert f(None) == B.OK, name
+        assert f(ctypes.byref(ok)) == B.OK, name
+        for b in bad:
+            assert f(ctypes.byref(b)) == B.ERR_HYPER, (name, b.block, b.xcd_remap, b.wg_per_cu, b.generic_path)
+    # the ordinary validation still runs behind a valid shape
+    assert calls["eager"](ctypes.byref(ok), n=-1) == B.ERR_SHAPE
+    assert lib.diloco_outer_eager_shaped(P[0], 0, 2, 64, 64, P[0], P[2], P[3], 64, P[4], 0.7, 0.9, 1, 0, 1, None,
+                                         ctypes.byref(ok)) == B.ERR_ALIAS
+    assert lib.diloco_inner_adamw_shaped(P[0], P[1], P[2], P[3], 2, 64, 64, 0, 0, 4e-4, 1.0, 0.95, 1e-8, 0.1, 1,
+                                         None, None) == B.ERR_HYPER
+    # binding: tuples of 3 or 4, or a Launch
+    assert B._launch(None) is None
+    for l in ((64, 1, 2), (64, 1, 2, 1), ok):
+        assert B._launch(l) is not None
+    with pytest.raises(ValueError):
+        B._launch((64, 1))
+
+
+def test_the_thread_shape_is_thread_local(lib):
+    """diloco_tune sets the shape of the calling thread only: two threads that set different
+    values each read back their own, a new thread starts from the automatic choice, and the
+    main thread's values are untouched throughout."""
+    import threading
+    assert lib.diloco_tune(b"block", 128) == B.OK and lib.diloco_tune(b"wg_per_cu", 5) == B.OK
+    barrier = threading.Barrier(3)
+    seen = {}
+
+    def worker(name, block, cap):
+        first = (lib.diloco_tune_get(b"block"), lib.diloco_tune_get(b"wg_per_cu"))
+        if block is not None:
+            assert lib.diloco_tune(b"block", block) == B.OK and lib.diloco_tune(b"wg_per_cu", cap) == B.OK
+        barrier.wait()            # every thread has set its values before any reads them back
+        seen[name] = (first, (lib.diloco_tune_get(b"block"), lib.diloco_tune_get(b"wg_per_cu")))
+        barrier.wait()
+
+    threads = [threading.Thread(target=worker, args=a) for a in (("a", 64, 2), ("b", 512, 16), ("c", None, None))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    try:
+        assert seen["a"] == ((0, -1), (64, 2))
+        assert seen["b"] == ((0, -1), (512, 16))
+        assert seen["c"] == ((0, -1), (0, -1))
+        assert (lib.diloco_tune_get(b"block"), lib.diloco_tune_get(b"wg_per_cu")) == (128, 5)
+    finally:
+        assert lib.diloco_tune(b"block", 0) == B.OK and lib.diloco_tune(b"wg_per_cu", -1) == B.OK
 
 
 def test_binding_raises_with_status_text(lib):
-    class FakeTensor:
-        """Stands in for a device tensor: the call must fail in validation, before any launch."""
-        def __init__(self, ptr, shape, dtype):
-            self._p, self.shape, self.dtype = ptr, shape, dtype
-        def data_ptr(self):
-            return self._p
-        def dim(self):
-            return len(self.shape)
-        def stride(self, k):
-            return self.shape[1] if k == 0 else 1
-        def numel(self):
-            return self.shape[0] * (self.shape[1] if len(self.shape) > 1 else 1)
-    import torch
-    th = FakeTensor(P[0], (2, 64), torch.float32)
-    a = FakeTensor(P[0], (2, 64), torch.float32)      # aliases theta
-    u = FakeTensor(P[2], (2, 64), torch.float32)
-    pl = FakeTensor(P[3], (2, 64), torch.float32)
-    pm = FakeTensor(P[4], (64,), torch.float32)
     with pytest.raises(B.DilocoError) as ei:
-        B.outer_eager(th, a, u, pl, pm, outer_lr=0.7, outer_momentum=0.9, stream=_NullStream())
+        B._check("diloco_outer_eager", eager(lib, a=P[0]))          # anchor on top of theta
     assert ei.value.status == B.ERR_ALIAS and "overlap" in str(ei.value)
+    B._check("diloco_outer_eager", eager(lib, n=0))
+
+
+def test_binding_refuses_what_the_library_cannot_check():
+    """The C ABI sees addresses only.  Host tensors, wrong dtypes, short rows, mismatched strides
+    and tensors that are not tensors are refused in Python, before any pointer is handed over."""
+    import torch
+    M, n = 3, 100
+    th = torch.zeros((M, n))
+    kw = dict(outer_lr=0.7, outer_momentum=0.9)
+    # host memory: every entry point refuses, nothing is launched (there is no GPU here anyway)
+    with pytest.raises(TypeError, match="GPU memory only"):
+        B.outer_eager(th, th.clone(), th.clone(), th.clone(), torch.zeros(n), **kw)
+    with pytest.raises(TypeError, match="GPU memory only"):
+        B.inner_adamw(th, th.clone(), th.clone(), th.clone(), lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8,
+                      weight_decay=0.0, step=1)
+    with pytest.raises(TypeError, match="GPU memory only"):
+        B.outer_sync(th, torch.zeros(n), torch.zeros(n), **kw)
+    with pytest.raises(TypeError, match="GPU memory only"):
+        B.reset(th, torch.zeros(n))
+    with pytest.raises(TypeError, match="GPU memory only"):
+        B.sim_stream_copy(torch.zeros(8), torch.zeros(8))
+    with pytest.raises(ValueError):
+        B.outer_eager(torch.zeros(n), th, th, th, torch.zeros(n), **kw)          # theta is not [M, n]
+    # the checks themselves, on host tensors
+    a = B._Args("unit", require_gpu=False)
+    assert a.rows(th, "theta", M, n, B._PARAM_DTYPES) == n
+    assert a.rows(torch.zeros((M, n + 5))[:, 2:], "view", M, n) == n + 5
+    a.vec(torch.zeros(n), "vec", n)
+    a.vec(None, "opt", n, optional=True)
+    with pytest.raises(TypeError, match="torch tensor"):
+        a.rows([[0.0] * n] * M, "theta", M, n)
+    with pytest.raises(TypeError, match="float64"):
+        a.rows(torch.zeros((M, n), dtype=torch.float64), "anchor", M, n)
+    with pytest.raises(TypeError, match="bfloat16"):
+        a.rows(torch.zeros((M, n), dtype=torch.bfloat16), "anchor", M, n)           # outer state is fp32
+    with pytest.raises(ValueError, match=r"M=3"):
+        a.rows(torch.zeros((M + 1, n)), "vel", M, n)
+    with pytest.raises(ValueError, match="rows of 100"):
+        a.rows(th, "theta", M, n + 1)                                               # n beyond the row
+    with pytest.raises(ValueError, match="row stride"):
+        a.rows(torch.zeros((M, n + 4)), "vel", M, n, stride=n)
+    with pytest.raises(ValueError, match="contiguous rows"):
+        a.rows(torch.zeros((n, M)).t(), "theta", M, n)
+    with pytest.raises(ValueError, match="holds 99"):
+        a.vec(torch.zeros(n - 1), "prev_mean", n)
+    with pytest.raises(ValueError, match="contiguous"):
+        a.vec(torch.zeros(2 * n)[::2], "prev_mean", n)
+    with pytest.raises(TypeError, match="required"):
+        a.vec(None, "anchor", n)
+    if torch.cuda.is_available() and torch.cuda.device_count() > 1:
+        b = B._Args("unit")
+        b.vec(torch.zeros(4, device="cuda:0"), "x", 4)
+        with pytest.raises(ValueError, match="other arguments on"):
+            b.vec(torch.zeros(4, device="cuda:1"), "y", 4)
+    # the packed state must hold diloco_packed_state_elems(M, n) floats
+    with pytest.raises(ValueError, match="holds 8"):
+        B._Args("unit", require_gpu=False).vec(torch.zeros(8), "state", B.packed_state_elems(M, n))
 
 
 class _NullStream:
@@ -262,7 +370,9 @@ def test_headers_are_plain_c_and_a_c_program_links_against_the_library(lib, tmp_
         "int main(void) {\n"
         "    /* validation only: no launch, no GPU needed */\n"
         "    int rc = diloco_outer_eager(NULL, DILOCO_F32, 2, 64, 64, NULL, NULL, NULL, 64, NULL, 0.7, 0.9, 1,\n"
-        "                                (diloco_variant)(DILOCO_EAGER | DILOCO_COMM_EXMY(2, 1, 11)), 1, NULL);\n"
+        "                                DILOCO_EAGER | DILOCO_COMM_EXMY(2, 1, 11) | DILOCO_STATE_NO_MEAN, 1, NULL);\n"
+        "    diloco_launch shape = {256, 1, 2, 0};\n"
+        "    rc += 100 * diloco_outer_eager_packed_shaped(NULL, DILOCO_F32, 2, 64, 64, NULL, 0.7, 0.9, 1, DILOCO_EAGER, 1, NULL, &shape);\n"
         '    printf("%d %d %s %lld %d\\n", diloco_version(), rc, diloco_strerror(rc),\n'
         "           (long long)diloco_packed_state_elems(8, 8193), DILOCO_SIM_MAX_FUSED_STEPS);\n"
         "    return 0;\n}\n")
@@ -271,5 +381,5 @@ def test_headers_are_plain_c_and_a_c_program_links_against_the_library(lib, tmp_
     subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe), "-L", libdir,
                     "-l:" + os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=2)
-    assert int(out[0]) >= 100 and int(out[1]) == B.ERR_NULL
+    assert int(out[0]) >= 100 and int(out[1]) == 101 * B.ERR_NULL
     assert out[2].strip().endswith(f"{2 * 25 * 8192} 64")

@@ -11,7 +11,9 @@ import torch
 import paper_2502_12996_amd as d
 from oracle import diloco_oracle as O
 from paper_2502_12996_amd import workloads as W
-from tests.util import TOL_BF16, TOL_F32, assert_close, rel_err
+from tests import cases
+from tests.util import (TOL_BF16, TOL_F32, adamw_scales, assert_close, checked_adamw, checked_eager,
+                        checked_standard, quadratic_scales)
 
 pytestmark = pytest.mark.gpu
 
@@ -40,9 +42,7 @@ def run_eager_case(M, n, *, bf16=False, variant="eager", apply=True, nesterov=Tr
     if misalign:   # shift every buffer by `misalign` elements: still element-aligned, not 16-byte aligned
         st = {k: (v[:, misalign:] if v.dim() == 2 else v) for k, v in st.items()}
     ref = {k: W.to_f64(v[..., :n]) for k, v in st.items()}
-    fn = O.outer_eager if variant == "eager" else O.outer_delayed
-    fn(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU,
-       nesterov, apply)
+    S = checked_eager(ref, ETA, MU, nesterov, apply, variant)
     full = {k: v.to(DEV) for k, v in W.outer_state(wl, n, seed=seed, stride=stride + misalign).items()}
     g = {k: (v[:, misalign:] if (misalign and v.dim() == 2) else v) for k, v in full.items()}
     before = {k: v.clone() for k, v in full.items()}
@@ -54,7 +54,7 @@ def run_eager_case(M, n, *, bf16=False, variant="eager", apply=True, nesterov=Tr
     for k in ref:
         got = W.to_f64(g[k][..., :n])
         tol = TOL_BF16 if (bf16 and k == "theta") else TOL_F32
-        worst = max(worst, assert_close(got, ref[k], tol, f"{variant} M={M} n={n} {k}") / tol)
+        worst = max(worst, assert_close(got, ref[k], tol, f"{variant} M={M} n={n} {k}", scale=S[k]) / tol)
         # columns outside [0, n) of every row (padding, and the skipped leading elements) untouched
         if g[k].dim() == 2 and (pad or misalign):
             assert torch.equal(full[k][:, misalign + n:], before[k][:, misalign + n:]), k
@@ -131,10 +131,9 @@ def test_eager_generic_paths_agree_bitwise(M):
         assert torch.equal(out[0][k], out[2][k]), k
     st = W.outer_state(wl_for(M, n), n, seed=71)
     ref = {k: W.to_f64(v) for k, v in st.items()}
-    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU,
-                  True, True)
+    S = checked_eager(ref, ETA, MU)
     for k in ref:
-        assert_close(W.to_f64(out[0][k]), ref[k], TOL_F32, f"grouped kernel M={M} {k}")
+        assert_close(W.to_f64(out[0][k]), ref[k], TOL_F32, f"grouped kernel M={M} {k}", scale=S[k])
 
 
 @pytest.mark.parametrize("M,n", [(1000, 37), (65535, 5)])
@@ -143,13 +142,13 @@ def test_very_many_replicas(M, n):
     wl = wl_for(M, n)
     st = W.outer_state(wl, n, seed=89, stride=n + 3)
     ref = {k: W.to_f64(v[..., :n]) for k, v in st.items()}
-    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU, True, True)
+    S = checked_eager(ref, ETA, MU)
     g = {k: v.to(DEV) for k, v in st.items()}
     d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], n=n,
                   outer_lr=ETA, outer_momentum=MU)
     torch.cuda.synchronize()
     for k in ref:
-        assert_close(W.to_f64(g[k][..., :n]), ref[k], TOL_F32, f"eager M={M} {k}")
+        assert_close(W.to_f64(g[k][..., :n]), ref[k], TOL_F32, f"eager M={M} {k}", scale=S[k])
     if 3 * M + 1 <= 65535:
         pk = {k: v.to(DEV) for k, v in st.items()}
         state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
@@ -162,32 +161,34 @@ def test_very_many_replicas(M, n):
         for k in g:
             assert torch.equal(pk[k], g[k]), k
     else:
+        big = torch.empty(d.packed_state_elems(M, n), device=DEV)       # 6.4 GB: the size the call names
         with pytest.raises(d.DilocoError) as ei:
-            d.pack_state(torch.zeros(8, device=DEV), M, n, anchor=g["anchor"])
+            d.pack_state(big, M, n, anchor=g["anchor"])
         assert ei.value.status == d.binding.ERR_SHAPE
+        del big
     # standard outer step and reset
     st = W.outer_state(wl, n, seed=97)
     theta, a, u = st["theta"], st["anchor"][0].clone(), st["vel"][0].clone()
     rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
-    O.outer_standard(rt, ra, ru, ETA, MU, True)
+    _, S = checked_standard(rt, ra, ru, ETA, MU, True)
     gt, ga, gu = theta.to(DEV), a.to(DEV), u.to(DEV)
     d.outer_sync(gt, ga, gu, outer_lr=ETA, outer_momentum=MU)
     th2 = torch.zeros_like(gt)
     d.reset(th2, ga)
     torch.cuda.synchronize()
-    assert_close(W.to_f64(ga), ra, TOL_F32, f"sync anchor M={M}")
-    assert_close(W.to_f64(gu), ru, TOL_F32, f"sync vel M={M}")
+    assert_close(W.to_f64(ga), ra, TOL_F32, f"sync anchor M={M}", scale=S["anchor"])
+    assert_close(W.to_f64(gu), ru, TOL_F32, f"sync vel M={M}", scale=S["vel"])
     assert torch.equal(gt, ga.expand(M, n)) and torch.equal(th2, gt)
     # AdamW: grid.y = replica
     ad = W.adamw_state(wl, n, seed=101)
     refa = {k: W.to_f64(v) for k, v in ad.items()}
-    O.adamw_step(refa["theta"], refa["m1"], refa["m2"], refa["grad"], 3, 4e-4, 0.9, 0.95, 1e-8, 0.1)
+    S = checked_adamw(refa, 3, 4e-4, 0.9, 0.95, 1e-8, 0.1)
     ga = {k: v.to(DEV) for k, v in ad.items()}
     d.inner_adamw(ga["theta"], ga["m1"], ga["m2"], ga["grad"], lr=4e-4, beta1=0.9, beta2=0.95, eps=1e-8,
                   weight_decay=0.1, step=3)
     torch.cuda.synchronize()
     for k in ("theta", "m1", "m2"):
-        assert_close(W.to_f64(ga[k]), refa[k], TOL_F32, f"adamw M={M} {k}")
+        assert_close(W.to_f64(ga[k]), refa[k], TOL_F32, f"adamw M={M} {k}", scale=S[k])
     with pytest.raises(d.DilocoError) as ei:
         d.outer_sync(torch.zeros((65536, 4), device=DEV), torch.zeros(4, device=DEV), torch.zeros(4, device=DEV),
                      outer_lr=ETA, outer_momentum=MU)
@@ -233,15 +234,15 @@ def test_sync_outer_step(M, n, bf16):
     st = W.outer_state(wl, n, seed=13)
     theta, a, u = st["theta"], st["anchor"][0].clone(), st["vel"][0].clone()
     rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
-    rmean = O.outer_standard(rt, ra, ru, ETA, MU, True)
+    rmean, S = checked_standard(rt, ra, ru, ETA, MU, True)
     gt, ga, gu = theta.to(DEV), a.to(DEV), u.to(DEV)
     gm = torch.empty(n, device=DEV)
     d.outer_sync(gt, ga, gu, mean_out=gm, outer_lr=ETA, outer_momentum=MU)
     torch.cuda.synchronize()
-    assert_close(W.to_f64(ga), ra, TOL_F32, "sync anchor")
-    assert_close(W.to_f64(gu), ru, TOL_F32, "sync vel")
-    assert_close(W.to_f64(gm), rmean, TOL_F32, "sync mean")
-    assert_close(W.to_f64(gt), rt, TOL_BF16 if bf16 else TOL_F32, "sync theta")
+    assert_close(W.to_f64(ga), ra, TOL_F32, "sync anchor", scale=S["anchor"])
+    assert_close(W.to_f64(gu), ru, TOL_F32, "sync vel", scale=S["vel"])
+    assert_close(W.to_f64(gm), rmean, TOL_F32, "sync mean", scale=S["mean"])
+    assert_close(W.to_f64(gt), rt, TOL_BF16 if bf16 else TOL_F32, "sync theta", scale=S["theta"])
     assert torch.equal(gt, ga.to(gt.dtype).expand(M, n))
 
 
@@ -251,7 +252,7 @@ def test_sync_heavy_ball_misaligned_and_no_mean_out():
     st = W.outer_state(wl, n + 1, seed=17)
     theta, a, u = st["theta"][:, 1:], st["anchor"][0, 1:].clone(), st["vel"][0, 1:].clone()
     rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
-    O.outer_standard(rt, ra, ru, 0.4, 0.5, False)
+    _, S = checked_standard(rt, ra, ru, 0.4, 0.5, False)
     gfull = st["theta"].to(DEV)
     gt = gfull[:, 1:]
     gab, gub = torch.zeros(n + 1, device=DEV), torch.zeros(n + 1, device=DEV)
@@ -260,9 +261,9 @@ def test_sync_heavy_ball_misaligned_and_no_mean_out():
     gu.copy_(u)
     d.outer_sync(gt, ga, gu, n=n, outer_lr=0.4, outer_momentum=0.5, nesterov=False)
     torch.cuda.synchronize()
-    assert_close(W.to_f64(ga), ra, TOL_F32, "anchor")
-    assert_close(W.to_f64(gu), ru, TOL_F32, "vel")
-    assert_close(W.to_f64(gt), rt, TOL_F32, "theta")
+    assert_close(W.to_f64(ga), ra, TOL_F32, "anchor", scale=S["anchor"])
+    assert_close(W.to_f64(gu), ru, TOL_F32, "vel", scale=S["vel"])
+    assert_close(W.to_f64(gt), rt, TOL_F32, "theta", scale=S["theta"])
     assert torch.equal(gfull[:, 0].cpu(), st["theta"][:, 0])
 
 
@@ -275,7 +276,9 @@ def test_sync_momentum_off_lr_one_is_the_replica_average():
     gu = W.normal((n,), 1.0, tag="vel", seed=21).to(DEV)
     d.outer_sync(gt, ga, gu, outer_lr=1.0, outer_momentum=0.0)
     torch.cuda.synchronize()
-    assert_close(W.to_f64(ga), want, TOL_F32, "replica average")
+    a0 = W.to_f64(W.normal((n,), 0.02, tag="anchor", seed=21))
+    scale = np.abs(a0) + np.mean(np.abs(a0[None, :] - W.to_f64(theta)), axis=0)
+    assert_close(W.to_f64(ga), want, TOL_F32, "replica average", scale=scale)
 
 
 # ------------------------------------------------------------------ reset
@@ -308,8 +311,7 @@ def test_inner_adamw(pdt, gdt, M, n, pad, off, step):
     st = W.adamw_state(wl, n + off, seed=29, stride=n + off + pad, grad_dtype=gd)
     view = {k: v[:, off:off + n] for k, v in st.items()}
     ref = {k: W.to_f64(v) for k, v in view.items()}
-    O.adamw_step(ref["theta"], ref["m1"], ref["m2"], ref["grad"], step, wl.lr, wl.beta1, wl.beta2,
-                 wl.eps, wl.weight_decay)
+    S = checked_adamw(ref, step, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay)
     full = {k: v.to(DEV) for k, v in st.items()}
     before = {k: v.clone() for k, v in full.items()}
     g = {k: v[:, off:] for k, v in full.items()}
@@ -318,7 +320,7 @@ def test_inner_adamw(pdt, gdt, M, n, pad, off, step):
     torch.cuda.synchronize()
     tol = TOL_BF16 if pdt == "bf16" else TOL_F32
     for k in ("theta", "m1", "m2"):
-        assert_close(W.to_f64(g[k][:, :n]), ref[k], tol, f"adamw {k}")
+        assert_close(W.to_f64(g[k][:, :n]), ref[k], tol, f"adamw {k}", scale=S[k])
         assert torch.equal(full[k][:, off + n:], before[k][:, off + n:])
         assert torch.equal(full[k][:, :off], before[k][:, :off])
     assert torch.equal(full["grad"], before["grad"])
@@ -331,14 +333,15 @@ def test_inner_adamw_zero_state_first_step_and_zero_gradient():
     g[0, :10] = 0.0
     rt, rg = W.to_f64(th), W.to_f64(g)
     r1, r2 = np.zeros((M, n)), np.zeros((M, n))
+    S = adamw_scales(rt, r1, r2, rg, 1, 4e-4, 0.9, 0.95, 1e-8, 0.1)
     O.adamw_step(rt, r1, r2, rg, 1, 4e-4, 0.9, 0.95, 1e-8, 0.1)
     gt, gg = th.to(DEV), g.to(DEV)
     g1, g2 = torch.zeros((M, n), device=DEV), torch.zeros((M, n), device=DEV)
     d.inner_adamw(gt, g1, g2, gg, lr=4e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1)
     torch.cuda.synchronize()
-    assert_close(W.to_f64(gt), rt, TOL_F32, "theta")
-    assert_close(W.to_f64(g1), r1, TOL_F32, "m1")
-    assert_close(W.to_f64(g2), r2, TOL_F32, "m2")
+    assert_close(W.to_f64(gt), rt, TOL_F32, "theta", scale=S["theta"])
+    assert_close(W.to_f64(g1), r1, TOL_F32, "m1", scale=S["m1"])
+    assert_close(W.to_f64(g2), r2, TOL_F32, "m2", scale=S["m2"])
     assert np.isfinite(W.to_f64(gt)).all()
 
 
@@ -355,6 +358,7 @@ def test_quadratic_inner_step_and_loss(M, n, base):
     rt, r1, r2 = (W.to_f64(x[:, :n]) for x in (th, m1, m2))
     rh, rs = W.to_f64(h), W.to_f64(star)
     seed, step = 0xC0FFEE, 17
+    S = quadratic_scales(rt, r1, r2, rh, rs, wl.noise_std, seed, step, wl.lr, wl.beta1, wl.beta2, wl.eps, 0.0, base)
     O.quadratic_inner_step(rt, r1, r2, rh, rs, step, seed, wl.noise_std, wl.lr, wl.beta1, wl.beta2,
                            wl.eps, 0.0, index_base=base)
     gt, g1, g2, gh, gs = (x.to(DEV) for x in (th, m1, m2, h, star))
@@ -369,9 +373,9 @@ def test_quadratic_inner_step_and_loss(M, n, base):
     gt, g1, g2 = gt[:, :n], g1[:, :n], g2[:, :n]
     # the gradient noise goes through fp32 log / sincos: a few 1e-7 relative on z, which AdamW's
     # normalised step turns into the same relative error of the update (lr-sized), far inside 1e-6
-    assert_close(W.to_f64(gt), rt, TOL_F32, "theta")
-    assert_close(W.to_f64(g1), r1, TOL_F32, "m1")
-    assert_close(W.to_f64(g2), r2, TOL_F32, "m2")
+    assert_close(W.to_f64(gt), rt, TOL_F32, "theta", scale=S["theta"])
+    assert_close(W.to_f64(g1), r1, TOL_F32, "m1", scale=S["m1"])
+    assert_close(W.to_f64(g2), r2, TOL_F32, "m2", scale=S["m2"])
     want = O.quadratic_loss(O.mean_over_replicas(W.to_f64(gt)), rh, rs)
     assert abs(out.item() - want) <= 1e-12 * max(want, 1e-300)
 
@@ -404,13 +408,16 @@ def test_quadratic_fused_phase_equals_separate_steps_bitwise(M, n, base, first, 
         rt, r1, r2 = (W.to_f64(x[:, :n]) for x in (th, m1, m2))
         rh, rs = W.to_f64(h), W.to_f64(star)
         for t in range(first, first + steps):
+            if t == first + steps - 1:     # the operand scales of the last step
+                S = quadratic_scales(rt, r1, r2, rh, rs, wl.noise_std, 0xBEEF, t, wl.lr, wl.beta1, wl.beta2,
+                                     wl.eps, 0.0, base)
             O.quadratic_inner_step(rt, r1, r2, rh, rs, t, 0xBEEF, wl.noise_std, wl.lr, wl.beta1, wl.beta2,
                                    wl.eps, 0.0, index_base=base)
         # per-step differences of a few 1e-7 (fp32 log / sincos in the noise) add up over the steps
         tol = TOL_F32 * max(1, steps) ** 0.5 * 2
-        assert_close(W.to_f64(b[0][:, :n]), rt, tol, "theta after the phase")
-        assert_close(W.to_f64(b[1][:, :n]), r1, tol, "m1 after the phase")
-        assert_close(W.to_f64(b[2][:, :n]), r2, tol, "m2 after the phase")
+        assert_close(W.to_f64(b[0][:, :n]), rt, tol, "theta after the phase", scale=S["theta"])
+        assert_close(W.to_f64(b[1][:, :n]), r1, tol, "m1 after the phase", scale=S["m1"])
+        assert_close(W.to_f64(b[2][:, :n]), r2, tol, "m2 after the phase", scale=S["m2"])
 
 
 def test_quadratic_fused_phase_rejects_too_many_steps():
@@ -491,8 +498,7 @@ def test_eager_packed_against_the_checker_and_elementwise_path():
     M, n = 8, 50_003
     st = W.outer_state(wl_for(M, n), n, seed=47, stride=n + 2)      # odd theta stride: element-wise path
     ref = {k: W.to_f64(v[..., :n]) for k, v in st.items()}
-    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU,
-                  True, True)
+    S = checked_eager(ref, ETA, MU)
     g = {k: v.to(DEV) for k, v in st.items()}
     state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
     d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
@@ -502,7 +508,7 @@ def test_eager_packed_against_the_checker_and_elementwise_path():
                    prev_mean=g["prev_mean"])
     torch.cuda.synchronize()
     for k in ref:
-        assert_close(W.to_f64(g[k][..., :n]), ref[k], TOL_F32, f"packed {k}")
+        assert_close(W.to_f64(g[k][..., :n]), ref[k], TOL_F32, f"packed {k}", scale=S[k])
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -528,9 +534,7 @@ def test_eager_with_bf16_communication(M, variant, apply, packed):
     n = 30_005
     st = W.outer_state(wl_for(M, n), n, seed=59)
     ref = {k: W.to_f64(v) for k, v in st.items()}
-    fn = O.outer_eager if variant == "eager" else O.outer_delayed
-    fn(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU, True,
-       apply, comm="bf16")
+    S = checked_eager(ref, ETA, MU, True, apply, variant, comm="bf16")
     g = {k: v.to(DEV) for k, v in st.items()}
     var = (d.EAGER if variant == "eager" else d.DELAYED) | d.COMM_BF16
     if packed:
@@ -550,7 +554,7 @@ def test_eager_with_bf16_communication(M, variant, apply, packed):
     bf = g["prev_local"].to(torch.bfloat16).to(torch.float32)
     assert torch.equal(bf, g["prev_local"])
     for k in ref:
-        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"bf16 comm {variant} {k}")
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"bf16 comm {variant} {k}", scale=S[k])
 
 
 # ------------------------------------------------------------------ small floats on the wire (Section 3.2)
@@ -603,7 +607,7 @@ def test_exmy_rounding_is_bit_exact(fmt, packed):
     bad = np.nonzero(got != want)
     assert bad[0].size == 0, (fmt, xs.numpy()[bad][:5], got[bad][:5], want[bad][:5])
     assert np.array_equal(np.signbit(got), np.signbit(want))
-    assert_close(W.to_f64(D), want.mean(axis=0), TOL_F32, f"mean of {fmt}")
+    assert_close(W.to_f64(D), want.mean(axis=0), TOL_F32, f"mean of {fmt}", scale=np.abs(want).mean(axis=0))
 
 
 @pytest.mark.parametrize("M", [1, 2, 8, 9, 33])
@@ -616,9 +620,7 @@ def test_eager_with_exmy_communication(M, variant, apply, packed, misalign, fmt)
     cut = (lambda v: v[:, misalign:misalign + n] if v.dim() == 2 else v)
     st = {k: cut(v) for k, v in W.outer_state(wl, n, seed=61, stride=n + 8).items()}
     ref = {k: W.to_f64(v) for k, v in st.items()}
-    fn = O.outer_eager if variant == "eager" else O.outer_delayed
-    fn(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU, True,
-       apply, comm=("exmy",) + fmt)
+    S = checked_eager(ref, ETA, MU, True, apply, variant, comm=("exmy",) + fmt)
     g = {k: cut(v.to(DEV)) for k, v in W.outer_state(wl, n, seed=61, stride=n + 8).items()}
     var = (d.EAGER if variant == "eager" else d.DELAYED) | d.COMM_EXMY(*fmt)
     if packed:
@@ -636,7 +638,7 @@ def test_eager_with_exmy_communication(M, variant, apply, packed, misalign, fmt)
     assert np.array_equal(W.to_f64(g["prev_local"]), ref["prev_local"])        # codes: bit-exact
     assert len(np.unique(np.abs(ref["prev_local"]))) <= 1 << (fmt[0] + fmt[1])
     for k in ref:
-        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"exmy {fmt} comm {variant} {k}")
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"exmy {fmt} comm {variant} {k}", scale=S[k])
 
 
 @pytest.mark.parametrize("M", [1, 3, 8, 12])
@@ -649,15 +651,15 @@ def test_standard_outer_step_with_quantised_communication(M, comm, misalign):
     theta = st["theta"][:, misalign:misalign + n]
     a, u = st["anchor"][0, :n].clone(), st["vel"][0, :n].clone()
     rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
-    want_mean = O.outer_standard(rt, ra, ru, ETA, MU, True, comm="bf16" if comm == "bf16" else ("exmy",) + comm)
+    want_mean, S = checked_standard(rt, ra, ru, ETA, MU, True, comm=cases.oracle_comm(comm))
     gt = st["theta"].to(DEV)[:, misalign:misalign + n]
     ga, gu, gm = a.to(DEV), u.to(DEV), torch.zeros(n, device=DEV)
     d.outer_sync(gt, ga, gu, n=n, mean_out=gm, outer_lr=ETA, outer_momentum=MU,
                  comm=d.COMM_BF16 if comm == "bf16" else d.COMM_EXMY(*comm))
     torch.cuda.synchronize()
-    assert_close(W.to_f64(gm), want_mean, TOL_F32, "mean of the rounded outer gradients")
-    assert_close(W.to_f64(ga), ra, TOL_F32, "anchor")
-    assert_close(W.to_f64(gu), ru, TOL_F32, "vel")
+    assert_close(W.to_f64(gm), want_mean, TOL_F32, "mean of the rounded outer gradients", scale=S["mean"])
+    assert_close(W.to_f64(ga), ra, TOL_F32, "anchor", scale=S["anchor"])
+    assert_close(W.to_f64(gu), ru, TOL_F32, "vel", scale=S["vel"])
     assert torch.equal(gt, ga.expand(M, n))
     # the mean of M values of a coarse grid sits on the grid refined by 1/M: fp4 has 8 magnitudes
     if comm != "bf16" and comm[0] + comm[1] <= 3:
@@ -677,7 +679,7 @@ def test_standard_outer_step_with_quantised_communication(M, comm, misalign):
 
 
 # ------------------------------------------------------------------ eager step that does not keep the previous mean
-@pytest.mark.parametrize("M", [1, 2, 3, 8])
+@pytest.mark.parametrize("M", [1, 2, 3, 8, 9, 16, 24, 26, 27, 33, 42])
 @pytest.mark.parametrize("layout,misalign,bf16", [("rows", 0, False), ("rows", 1, False), ("packed", 0, False),
                                                    ("packed", 0, True)])
 @pytest.mark.parametrize("comm", [0, "bf16"])
@@ -719,13 +721,13 @@ def test_eager_without_a_stored_mean_walks_the_same_trajectory_bit_for_bit(M, la
     assert (lean["prev_mean"] == 7.0).all() and not (plain["prev_mean"] == 7.0).any()
 
 
-@pytest.mark.parametrize("M", [1, 2, 5, 8])
+@pytest.mark.parametrize("M", [1, 2, 5, 8, 9, 24, 25, 33, 60])
 @pytest.mark.parametrize("packed", [False, True])
 def test_eager_without_a_stored_mean_against_the_checker(M, packed):
     n = 20_003
     st = W.outer_state(wl_for(M, n), n, seed=107)
     ref = {k: W.to_f64(v) for k, v in st.items()}
-    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], None, ETA, MU, True, True)
+    S = checked_eager(ref, ETA, MU, no_mean=True)
     g = {k: v.to(DEV) for k, v in st.items()}
     g["prev_mean"].fill_(-3.0)          # must not matter
     if packed:
@@ -740,33 +742,46 @@ def test_eager_without_a_stored_mean_against_the_checker(M, packed):
                       outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
     torch.cuda.synchronize()
     for k in ("theta", "anchor", "vel", "prev_local"):
-        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"no stored mean M={M} {k}")
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"no stored mean M={M} {k}", scale=S[k])
     assert (g["prev_mean"] == -3.0).all()
 
 
 def test_eager_without_a_stored_mean_is_refused_where_it_cannot_work():
-    g = _rows(9, 64, 3)
-    with pytest.raises(d.DilocoError) as ei:      # no register kernel beyond 8 replicas
-        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], outer_lr=ETA,
-                      outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
-    assert ei.value.status == d.binding.ERR_SHAPE
     g = _rows(2, 64, 3)
     with pytest.raises(d.DilocoError) as ei:      # the delayed step reads nothing but the stored mean
         d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], outer_lr=ETA,
                       outer_momentum=MU, variant=d.DELAYED | d.STATE_NO_MEAN)
     assert ei.value.status == d.binding.ERR_DTYPE
-    d.tune("generic_path", 2)                      # a forced generic path gives way to the register kernel
-    try:
-        a, b = _rows(4, 4099, 5), _rows(4, 4099, 5)
-        d.outer_eager(a["theta"], a["anchor"], a["vel"], a["prev_local"], a["prev_mean"], outer_lr=ETA,
-                      outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
-    finally:
-        d.tune("generic_path", 0)
-    d.outer_eager(b["theta"], b["anchor"], b["vel"], b["prev_local"], b["prev_mean"], outer_lr=ETA,
-                  outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN)
+
+
+@pytest.mark.parametrize("M", [4, 8, 9, 24, 26, 27, 53, 54, 70])
+def test_eager_without_a_stored_mean_every_kernel_path_agrees_bitwise(M):
+    """The register kernel (M <= 8), the grouped kernel staging all, some (24 with the third LDS slot;
+    53 when forced to one workgroup per CU) or none of the replicas, and the element-wise kernel
+    form the previous mean from the previous locals in the same order: same bits."""
+    n = 12_291
+    out = []
+    for path, pad in ((0, 0), (1, 0), (2, 0), (0, 2)):       # pad 2: odd stride, element-wise kernel
+        g = _rows(M, n, 5, pad=pad)
+        g["prev_mean"].fill_(9.0)
+        d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], n=n, outer_lr=ETA,
+                      outer_momentum=MU, variant=d.EAGER | d.STATE_NO_MEAN, launch=(0, 0, -1, path))
+        torch.cuda.synchronize()
+        assert (g["prev_mean"] == 9.0).all()
+        out.append(g)
+    for other in out[1:]:
+        for k in ("theta", "anchor", "vel", "prev_local"):
+            assert torch.equal(out[0][k][:, :n], other[k][:, :n]), k
+    # and the plain call with the mean the flag-less call would have stored
+    g = _rows(M, n, 5)
+    s = g["prev_local"][0].double()
+    for m in range(1, M):
+        s += g["prev_local"][m].double()
+    g["prev_mean"].copy_((s * (1.0 / M)).float())
+    d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], outer_lr=ETA, outer_momentum=MU)
     torch.cuda.synchronize()
-    for k in a:
-        assert torch.equal(a[k], b[k]), k
+    for k in ("theta", "anchor", "vel", "prev_local"):
+        assert torch.equal(out[0][k], g[k]), k
 
 
 @pytest.mark.parametrize("bits", [0x200, 0x800, 0x1000, 1 << 28, 0x100 | 0x200 | (4 << 12) | (3 << 16),
@@ -840,65 +855,47 @@ def test_every_launch_shape_gives_the_same_bits(launch_shape):
     wl = wl_for(3, n)
     ad = W.adamw_state(wl, n, seed=79)
     ref = {k: W.to_f64(v) for k, v in ad.items()}
-    O.adamw_step(ref["theta"], ref["m1"], ref["m2"], ref["grad"], 5, wl.lr, wl.beta1, wl.beta2, wl.eps,
-                 wl.weight_decay)
+    S = checked_adamw(ref, 5, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay)
     g = {k: v.to(DEV) for k, v in ad.items()}
     d.inner_adamw(g["theta"], g["m1"], g["m2"], g["grad"], lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2,
                   eps=wl.eps, weight_decay=wl.weight_decay, step=5)
     torch.cuda.synchronize()
     for k in ("theta", "m1", "m2"):
-        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"adamw {k} at shape {launch_shape}")
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"adamw {k} at shape {launch_shape}", scale=S[k])
     st = W.outer_state(wl, n, seed=83)
     theta, a, u = st["theta"], st["anchor"][0].clone(), st["vel"][0].clone()
     rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
-    O.outer_standard(rt, ra, ru, ETA, MU, True)
+    _, S = checked_standard(rt, ra, ru, ETA, MU, True)
     gt, ga, gu = theta.to(DEV), a.to(DEV), u.to(DEV)
     d.outer_sync(gt, ga, gu, outer_lr=ETA, outer_momentum=MU)
     th2 = torch.zeros_like(gt)
     d.reset(th2, ga)
     torch.cuda.synchronize()
-    assert_close(W.to_f64(ga), ra, TOL_F32, "sync anchor")
-    assert_close(W.to_f64(gu), ru, TOL_F32, "sync vel")
+    assert_close(W.to_f64(ga), ra, TOL_F32, "sync anchor", scale=S["anchor"])
+    assert_close(W.to_f64(gu), ru, TOL_F32, "sync vel", scale=S["vel"])
     assert torch.equal(gt, ga.expand(3, n)) and torch.equal(th2, gt)
 
 
 # ------------------------------------------------------------------ seeded sweep over valid argument combinations
-def _random_case(rng):
-    M = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 11, 17, 42]))
-    n = int(rng.choice([1, 3, 4, 63, 64, 257, 1000, 4097, 8191, 8192, 8193, 20_001]))
-    variant = str(rng.choice(["eager", "delayed"]))
-    case = dict(M=M, n=n, variant=variant, apply=bool(rng.integers(0, 2)), nesterov=bool(rng.integers(0, 2)),
-                bf16=bool(rng.integers(0, 2)), packed=bool(rng.integers(0, 2)), pad=int(rng.choice([0, 1, 4, 6])),
-                comm=[None, "bf16", (2, 1, 11), (4, 3, 16), (5, 2, 24)][int(rng.integers(0, 5))],
-                no_mean=bool(rng.integers(0, 2)) and variant == "eager" and M <= 8,
-                shape=[(0, 0, -1), (64, 1, 2), (256, 0, 0), (128, 1, 3), (512, 0, 1)][int(rng.integers(0, 5))],
-                eta=float(rng.choice([0.7, 1.0, 0.1])), mu=float(rng.choice([0.9, 0.0, 0.5])))
-    case["misalign"] = 0 if case["packed"] else int(rng.choice([0, 0, 1, 2]))
-    return case
+EAGER_SWEEP_CHUNKS, STANDARD_SWEEP_CHUNKS = 88, 44
 
 
-@pytest.mark.parametrize("chunk", range(8))
+@pytest.mark.parametrize("chunk", range(EAGER_SWEEP_CHUNKS))
 def test_seeded_sweep_of_valid_eager_calls_matches_the_checker(chunk):
     """25 argument combinations per chunk, drawn from a fixed seed: replica counts on every kernel
     path, ragged and tiny sizes, both layouts, misaligned rows, bf16 replicas, every wire format,
     with and without the stored mean, first boundary or not, several launch shapes."""
-    rng = np.random.default_rng(1000 + chunk)
-    for _ in range(25):
-        c = _random_case(rng)
+    rng = np.random.default_rng(cases.EAGER_SWEEP_SEED + chunk)
+    for _ in range(cases.EAGER_SWEEP_DRAWS):
+        c = cases.random_eager_case(rng)
         M, n, mis = c["M"], c["n"], c["misalign"]
         wl = wl_for(M, n, c["bf16"])
         stride = ((n + c["pad"] + mis + 3) & ~3) if c["packed"] else n + c["pad"] + mis
         cut = (lambda v: v[:, mis:mis + n] if v.dim() == 2 else v)
-        host = W.outer_state(wl, n, seed=300 + chunk, stride=stride)
+        host = W.outer_state(wl, n, seed=cases.EAGER_STATE_SEED + chunk, stride=stride)
         ref = {k: W.to_f64(cut(v)) for k, v in host.items()}
-        comm = "f32" if c["comm"] is None else ("bf16" if c["comm"] == "bf16" else ("exmy",) + c["comm"])
-        fn = O.outer_eager if c["variant"] == "eager" else O.outer_delayed
-        if c["no_mean"]:
-            O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], None, c["eta"], c["mu"],
-                          c["nesterov"], c["apply"], comm=comm)
-        else:
-            fn(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], c["eta"], c["mu"],
-               c["nesterov"], c["apply"], comm=comm)
+        S = checked_eager(ref, c["eta"], c["mu"], c["nesterov"], c["apply"], c["variant"],
+                          comm=cases.oracle_comm(c["comm"]), no_mean=c["no_mean"])
         full = {k: v.to(DEV) for k, v in host.items()}
         g = {k: cut(v) for k, v in full.items()}
         before_mean = g["prev_mean"].clone()
@@ -926,37 +923,34 @@ def test_seeded_sweep_of_valid_eager_calls_matches_the_checker(chunk):
                 assert torch.equal(g[k], before_mean), c
                 continue
             tol = TOL_BF16 if (c["bf16"] and k == "theta") else TOL_F32
-            assert_close(W.to_f64(g[k]), ref[k], tol, f"{c} {k}")
+            assert_close(W.to_f64(g[k]), ref[k], tol, f"{c} {k}", scale=S[k])
         if c["comm"] is not None:
             assert np.array_equal(W.to_f64(g["prev_local"]), ref["prev_local"]), c
 
 
-@pytest.mark.parametrize("chunk", range(4))
+@pytest.mark.parametrize("chunk", range(STANDARD_SWEEP_CHUNKS))
 def test_seeded_sweep_of_valid_standard_and_adamw_calls_matches_the_checker(chunk):
-    rng = np.random.default_rng(2000 + chunk)
-    for _ in range(20):
-        M = int(rng.choice([1, 2, 3, 4, 7, 8, 9, 12, 16, 33]))
-        n = int(rng.choice([1, 3, 4, 64, 257, 4097, 8193, 20_001]))
-        bf16, mis, pad = bool(rng.integers(0, 2)), int(rng.choice([0, 0, 1, 3])), int(rng.choice([0, 1, 4]))
-        comm = [None, "bf16", (2, 1, 11), (4, 3, 16)][int(rng.integers(0, 4))]
-        shape = [(0, 0, -1), (64, 1, 2), (256, 0, 0), (128, 1, 3), (512, 0, 1)][int(rng.integers(0, 5))]
-        eta, mu, nest = float(rng.choice([0.7, 1.0])), float(rng.choice([0.9, 0.0])), bool(rng.integers(0, 2))
+    """20 argument combinations per chunk for the standard outer step and the AdamW sweep.  Chunk 27
+    holds the one-element draw whose velocity update cancels 2000-fold (tests/test_error_metric.py)."""
+    rng = np.random.default_rng(cases.STANDARD_SWEEP_SEED + chunk)
+    for _ in range(cases.STANDARD_SWEEP_DRAWS):
+        c = cases.random_standard_adamw_case(rng)
+        M, n, bf16, mis, pad, comm = c["M"], c["n"], c["bf16"], c["misalign"], c["pad"], c["comm"]
+        eta, mu, nest, step = c["eta"], c["mu"], c["nesterov"], c["step"]
         wl = wl_for(M, n, bf16)
         cut = (lambda v: v[:, mis:mis + n])
-        host = W.outer_state(wl, n, seed=400 + chunk, stride=n + pad + mis)
+        host = W.outer_state(wl, n, seed=cases.STANDARD_STATE_SEED + chunk, stride=n + pad + mis)
         a, u = host["anchor"][0, :n].clone(), host["vel"][0, :n].clone()
         rt, ra, ru = W.to_f64(cut(host["theta"])), W.to_f64(a), W.to_f64(u)
-        want = O.outer_standard(rt, ra, ru, eta, mu, nest,
-                                comm="f32" if comm is None else ("bf16" if comm == "bf16" else ("exmy",) + comm))
+        want, S = checked_standard(rt, ra, ru, eta, mu, nest, comm=cases.oracle_comm(comm))
         gt = cut(host["theta"].to(DEV))
         ga, gu, gm = a.to(DEV), u.to(DEV), torch.zeros(n, device=DEV)
-        ad = W.adamw_state(wl, n, seed=500 + chunk, stride=n + pad + mis,
-                           grad_dtype=torch.bfloat16 if (bf16 and rng.integers(0, 2)) else torch.float32)
+        ad = W.adamw_state(wl, n, seed=cases.ADAMW_STATE_SEED + chunk, stride=n + pad + mis,
+                           grad_dtype=torch.bfloat16 if c["grad_bf16"] else torch.float32)
         refa = {k: W.to_f64(cut(v)) for k, v in ad.items()}
-        step = int(rng.choice([1, 2, 31, 1000]))
-        O.adamw_step(refa["theta"], refa["m1"], refa["m2"], refa["grad"], step, 4e-4, 0.9, 0.95, 1e-8, 0.1)
+        Sa = checked_adamw(refa, step, 4e-4, 0.9, 0.95, 1e-8, 0.1)
         gad = {k: cut(v.to(DEV)) for k, v in ad.items()}
-        set_shape(*shape)
+        set_shape(*c["shape"])
         try:
             d.outer_sync(gt, ga, gu, n=n, mean_out=gm, outer_lr=eta, outer_momentum=mu, nesterov=nest,
                          comm=None if comm is None else (d.COMM_BF16 if comm == "bf16" else d.COMM_EXMY(*comm)))
@@ -965,13 +959,40 @@ def test_seeded_sweep_of_valid_standard_and_adamw_calls_matches_the_checker(chun
         finally:
             set_shape(*DEFAULT_SHAPE)
         torch.cuda.synchronize()
-        tag = f"M={M} n={n} bf16={bf16} mis={mis} comm={comm} shape={shape}"
-        assert_close(W.to_f64(gm), want, TOL_F32, f"standard mean {tag}")
-        assert_close(W.to_f64(ga), ra, TOL_F32, f"standard anchor {tag}")
-        assert_close(W.to_f64(gu), ru, TOL_F32, f"standard vel {tag}")
+        tag = f"M={M} n={n} bf16={bf16} mis={mis} comm={comm} shape={c['shape']}"
+        assert_close(W.to_f64(gm), want, TOL_F32, f"standard mean {tag}", scale=S["mean"])
+        assert_close(W.to_f64(ga), ra, TOL_F32, f"standard anchor {tag}", scale=S["anchor"])
+        assert_close(W.to_f64(gu), ru, TOL_F32, f"standard vel {tag}", scale=S["vel"])
         assert torch.equal(gt, ga.to(gt.dtype).expand(M, n)), tag
         for k in ("theta", "m1", "m2"):
-            assert_close(W.to_f64(gad[k]), refa[k], TOL_BF16 if bf16 else TOL_F32, f"adamw {k} {tag} step={step}")
+            assert_close(W.to_f64(gad[k]), refa[k], TOL_BF16 if bf16 else TOL_F32, f"adamw {k} {tag} step={step}",
+                         scale=Sa[k])
+
+
+def test_the_one_element_draw_whose_velocity_cancels():
+    """Regression case: chunk 27, draw 7 of the sweep above on its own (M = 8, n = 1, heavy ball,
+    eta = 1, mu = 0.9): mu u + Delta leaves 1.8e-7 of two terms of 3.4e-4.  The library's value is the
+    float32 evaluation of Algorithm 1 line 10 to the bit, and within 1e-6 of the operand scale."""
+    c = cases.standard_sweep_case(27, 7)
+    assert (c["M"], c["n"], c["eta"], c["mu"], c["nesterov"]) == (8, 1, 1.0, 0.9, False)
+    wl = wl_for(c["M"], c["n"])
+    host = W.outer_state(wl, 1, seed=cases.STANDARD_STATE_SEED + 27, stride=1 + c["pad"])
+    a, u = host["anchor"][0, :1].clone(), host["vel"][0, :1].clone()
+    rt, ra, ru = W.to_f64(host["theta"][:, :1]), W.to_f64(a), W.to_f64(u)
+    want, S = checked_standard(rt, ra, ru, c["eta"], c["mu"], c["nesterov"])
+    gt, ga, gu, gm = host["theta"].to(DEV)[:, :1], a.to(DEV), u.to(DEV), torch.zeros(1, device=DEV)
+    d.outer_sync(gt, ga, gu, n=1, mean_out=gm, outer_lr=c["eta"], outer_momentum=c["mu"], nesterov=False)
+    torch.cuda.synchronize()
+    assert_close(W.to_f64(gu), ru, TOL_F32, "velocity", scale=S["vel"])
+    assert_close(W.to_f64(ga), ra, TOL_F32, "outer parameters", scale=S["anchor"])
+    assert_close(W.to_f64(gm), want, TOL_F32, "mean", scale=S["mean"])
+    # the float32 evaluation, in the library's order: float32 differences, float64 sum rounded once, one fma
+    delta = (a.numpy()[None, :] - host["theta"][:, :1].numpy()).astype(np.float32)
+    dbar = (np.sum(delta.astype(np.float64), axis=0) / 8).astype(np.float32)
+    u32 = (np.float64(np.float32(0.9)) * u.numpy().astype(np.float64) + dbar.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(gm.cpu().numpy(), dbar) and np.array_equal(gu.cpu().numpy(), u32)
+    # and that value misses 1e-6 of |u| by a wide margin: the cancellation, not the kernel
+    assert abs(float(u32[0]) - ru[0]) / abs(ru[0]) > 5e-5
 
 
 # ------------------------------------------------------------------ HIP graph capture
