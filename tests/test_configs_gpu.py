@@ -12,7 +12,9 @@ import torch
 import paper_2502_12996_amd as d
 from oracle import diloco_oracle as O
 from paper_2502_12996_amd import workloads as W
-from tests.util import TOL_BF16, TOL_F32, assert_close, rel_err
+from tests.streamed import f64 as SF, stream_chunks
+from tests.util import (TOL_BF16, TOL_F32, assert_close, checked_adamw, checked_eager, checked_standard, rel_err,
+                        scaled_err)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -108,7 +110,7 @@ def chunks_for(wl, size=1 << 13):
     bl = tab[-1][1]                     # start of the embedding
     starts = [0, b1 - size // 2, (n // 2) & ~3, bl - size // 2, n - size + 0]
     out = [(s, s + size) for s in starts]
-    out.append((n - 1001, n))           # ragged: odd start, odd length
+    out.append((n - 4099, n))           # ragged: odd start, odd length
     return out
 
 
@@ -165,7 +167,15 @@ def test_t150m_thirty_inner_steps_then_eager_outer_step():
           f"per-call error / 1e-6 {worst_c:.3f}")
 
 
-# ------------------------------------------------------------------ configs 3 and 4: full size, per call
+# ------------------------------------------------------------------ configs 2, 3 and 4: full size, every index
+# Each call runs once on the configuration's full buffers, in the launch shape the library picks
+# (and, for the packed eager step, in the shapes the benchmark chooses from); the inputs are kept in
+# a second set of device buffers, and EVERY index of every output buffer is then compared with the
+# checker, chunk by chunk (tests/streamed.py).  Nothing is sampled.
+FULL = ["t150m", "t550m", "t2b4_bf16"]
+PACKED_SHAPES = [None, (256, 0, 0), (64, 1, 3), (512, 1, 0), (256, 1, 1), (64, 0, 2), (64, 1, 4)]
+
+
 def big_chunks(n, size=1 << 14):
     starts = [0, 4 * 333_333, (n // 2) & ~3, n - size]
     if n > (1 << 31):
@@ -175,86 +185,126 @@ def big_chunks(n, size=1 << 14):
     return out
 
 
-@pytest.mark.parametrize("name", ["t550m", "t2b4_bf16"])
-def test_full_size_eager_outer_step_per_call(name):
+def report(name, what, worst, covered):
+    print(f"{name} {what}: all {covered} indices compared; worst error / tolerance per buffer: "
+          + ", ".join(f"{k} {v:.3f}" for k, v in sorted(worst.items())))
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_eager_outer_step_every_index(name):
+    """Algorithm 3 lines 7-12 at the configuration's size on caller rows, every index against the
+    checker; then the packed-state entry point in the benchmark's launch shapes, bit for bit against
+    the rows result over the whole buffers."""
     wl = W.WORKLOADS[name]
     M, n = wl.M, wl.n
     bf16 = wl.theta_dtype == "bf16"
     st = W.outer_state(wl, n, device=DEV)
-    chunks = big_chunks(n)
-    ref = [{k: f64(v[..., lo:hi]) for k, v in st.items()} for (lo, hi) in chunks]
+    saved = {k: v.clone() for k, v in st.items()}
     d.outer_eager(st["theta"], st["anchor"], st["vel"], st["prev_local"], st["prev_mean"],
                   outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
     torch.cuda.synchronize()
-    worst = 0.0
-    for r, (lo, hi) in zip(ref, chunks):
-        O.outer_eager(r["theta"], r["anchor"], r["vel"], r["prev_local"], r["prev_mean"],
-                      wl.outer_lr, wl.outer_momentum, True, True)
-        for k in r:
-            tol = TOL_BF16 if (bf16 and k == "theta") else TOL_F32
-            worst = max(worst, assert_close(f64(st[k][..., lo:hi]), r[k], tol, f"{name} {k} [{lo},{hi})") / tol)
-    # properties that hold at any size, on the whole buffers
+
+    def process(lo, hi):
+        ref = {k: SF(v[..., lo:hi]) for k, v in saved.items()}
+        S = checked_eager(ref, wl.outer_lr, wl.outer_momentum)
+        return {k: scaled_err(SF(st[k][..., lo:hi]), ref[k], S[k]) / (TOL_BF16 if (bf16 and k == "theta") else TOL_F32)
+                for k in ref}
+    worst, covered = stream_chunks(n, process)
+    report(name, "eager outer step (rows)", worst, covered)
+    assert max(worst.values()) <= 1.0, worst
+    # properties of the whole buffers
     assert torch.equal(st["theta"], st["anchor"].to(st["theta"].dtype))
     s = st["prev_local"][0].double()
     for m in range(1, M):
         s += st["prev_local"][m].double()
-    # the stored mean is the mean of the stored locals (M is a power of two here: exact division)
-    assert torch.equal((s / M).float(), st["prev_mean"])
-    print(f"{name}: worst per-call error / tolerance {worst:.3f}")
-    del st, s
+    assert torch.equal((s / M).float(), st["prev_mean"])       # M is a power of two here: exact division
+    del s
+    # the packed state: same inputs (regenerated from the seed), same bits out, in every shape
+    del saved
+    torch.cuda.empty_cache()
+    win = 1 << 24
+    tmp = {k: torch.empty((M, win), device=DEV) for k in ("anchor", "vel", "prev_local")}
+    tmp_mean = torch.empty(win, device=DEV)
+    for shape in PACKED_SHAPES:
+        inp = W.outer_state(wl, n, device=DEV)
+        state = torch.empty(d.packed_state_elems(M, n), device=DEV)
+        d.pack_state(state, M, n, anchor=inp["anchor"], vel=inp["vel"], prev_local=inp["prev_local"],
+                     prev_mean=inp["prev_mean"])
+        theta = inp["theta"]
+        del inp
+        torch.cuda.empty_cache()
+        d.outer_eager_packed(theta, state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum, launch=shape)
+        torch.cuda.synchronize()
+        assert torch.equal(theta, st["theta"]), shape
+        for lo in range(0, n, win):
+            cnt = min(win, n - lo)
+            d.unpack_state(d.packed_window(state, M, lo), M, cnt, anchor=tmp["anchor"], vel=tmp["vel"],
+                           prev_local=tmp["prev_local"], prev_mean=tmp_mean)
+            for k in tmp:
+                assert torch.equal(tmp[k][:, :cnt], st[k][:, lo:lo + cnt]), (shape, k, lo)
+            assert torch.equal(tmp_mean[:cnt], st["prev_mean"][lo:lo + cnt]), (shape, lo)
+        del theta, state
+        torch.cuda.empty_cache()
+        if name != "t550m":
+            break       # the benchmark's workload runs every shape, the others the library's choice
+    del st, tmp, tmp_mean
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name", ["t550m", "t2b4_bf16"])
-def test_full_size_inner_adamw_per_call(name):
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_inner_adamw_every_index(name):
+    """InnerOpt (line 5 of the listings) at the configuration's size, every index against the checker."""
     wl = W.WORKLOADS[name]
     n = wl.n
     bf16 = wl.theta_dtype == "bf16"
     st = W.adamw_state(wl, n, device=DEV, grad_dtype=torch.bfloat16 if bf16 else torch.float32)
-    chunks = big_chunks(n)
-    ref = [{k: f64(v[:, lo:hi]) for k, v in st.items()} for (lo, hi) in chunks]
+    saved = {k: st[k].clone() for k in ("theta", "m1", "m2")}
+    saved["grad"] = st["grad"]                                   # read only
     d.inner_adamw(st["theta"], st["m1"], st["m2"], st["grad"], lr=wl.lr, beta1=wl.beta1,
                   beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay, step=31)
     torch.cuda.synchronize()
     tol = TOL_BF16 if bf16 else TOL_F32
-    worst = 0.0
-    for r, (lo, hi) in zip(ref, chunks):
-        O.adamw_step(r["theta"], r["m1"], r["m2"], r["grad"], 31, wl.lr, wl.beta1, wl.beta2, wl.eps,
-                     wl.weight_decay)
-        for k in ("theta", "m1", "m2"):
-            worst = max(worst, assert_close(f64(st[k][:, lo:hi]), r[k], tol, f"{name} adamw {k} [{lo},{hi})") / tol)
-    print(f"{name}: worst AdamW per-call error / tolerance {worst:.3f}")
-    del st
+
+    def process(lo, hi):
+        ref = {k: SF(v[:, lo:hi]) for k, v in saved.items()}
+        S = checked_adamw(ref, 31, wl.lr, wl.beta1, wl.beta2, wl.eps, wl.weight_decay)
+        return {k: scaled_err(SF(st[k][:, lo:hi]), ref[k], S[k]) / tol for k in ("theta", "m1", "m2")}
+    worst, covered = stream_chunks(n, process)
+    report(name, "AdamW sweep", worst, covered)
+    assert max(worst.values()) <= 1.0, worst
+    del st, saved
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name", ["t150m", "t550m", "t2b4_bf16"])
-def test_full_size_standard_outer_step_per_call(name):
-    """Algorithm 1's outer step at the configurations' full sizes, shared outer parameters."""
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_standard_outer_step_every_index(name):
+    """Algorithm 1 lines 7-10 at the configuration's size (shared outer parameters), every index."""
     wl = W.WORKLOADS[name]
     M, n = wl.M, wl.n
     bf16 = wl.theta_dtype == "bf16"
     st = W.outer_state(wl, n, device=DEV)
     theta = st["theta"]
     a, u = st["anchor"][0].clone(), st["vel"][0].clone()
-    mean = torch.empty(n, device=DEV)
     del st
     torch.cuda.empty_cache()
-    chunks = big_chunks(n)
-    ref = [(f64(theta[:, lo:hi]), f64(a[lo:hi]), f64(u[lo:hi])) for (lo, hi) in chunks]
+    mean = torch.empty(n, device=DEV)
+    saved = (theta.clone(), a.clone(), u.clone())
     d.outer_sync(theta, a, u, mean_out=mean, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
     torch.cuda.synchronize()
-    worst = 0.0
-    for (rt, ra, ru), (lo, hi) in zip(ref, chunks):
-        dbar = O.outer_standard(rt, ra, ru, wl.outer_lr, wl.outer_momentum, True)
-        worst = max(worst, assert_close(f64(a[lo:hi]), ra, TOL_F32, f"{name} anchor [{lo},{hi})") / TOL_F32)
-        worst = max(worst, assert_close(f64(u[lo:hi]), ru, TOL_F32, f"{name} vel [{lo},{hi})") / TOL_F32)
-        worst = max(worst, assert_close(f64(mean[lo:hi]), dbar, TOL_F32, f"{name} mean [{lo},{hi})") / TOL_F32)
-    # at any size: every replica restarts from the new outer parameters
-    for m in range(M):
+
+    def process(lo, hi):
+        rt, ra, ru = SF(saved[0][:, lo:hi]), SF(saved[1][lo:hi]), SF(saved[2][lo:hi])
+        dbar, S = checked_standard(rt, ra, ru, wl.outer_lr, wl.outer_momentum, True)
+        return {"anchor": scaled_err(SF(a[lo:hi]), ra, S["anchor"]) / TOL_F32,
+                "vel": scaled_err(SF(u[lo:hi]), ru, S["vel"]) / TOL_F32,
+                "mean": scaled_err(SF(mean[lo:hi]), dbar, S["mean"]) / TOL_F32,
+                "theta": scaled_err(SF(theta[:, lo:hi]), rt, S["theta"]) / (TOL_BF16 if bf16 else TOL_F32)}
+    worst, covered = stream_chunks(n, process)
+    report(name, "standard outer step", worst, covered)
+    assert max(worst.values()) <= 1.0, worst
+    for m in range(M):                       # every replica restarts from the new outer parameters
         assert torch.equal(theta[m], a.to(theta.dtype))
-    print(f"{name}: worst standard outer step error / tolerance {worst:.3f}")
-    del theta, a, u, mean
+    del theta, a, u, mean, saved
     torch.cuda.empty_cache()
 
 
@@ -275,11 +325,10 @@ def test_t550m_packed_eager_step_with_fp4_communication():
                    prev_mean=st["prev_mean"])
     torch.cuda.synchronize()
     for r, (lo, hi) in zip(ref, chunks):
-        O.outer_eager(r["theta"], r["anchor"], r["vel"], r["prev_local"], r["prev_mean"],
-                      wl.outer_lr, wl.outer_momentum, True, True, comm=("exmy",) + fmt)
+        S = checked_eager(r, wl.outer_lr, wl.outer_momentum, comm=("exmy",) + fmt)
         assert np.array_equal(f64(st["prev_local"][:, lo:hi]), r["prev_local"])
         for k in r:
-            assert_close(f64(st[k][..., lo:hi]), r[k], TOL_F32, f"fp4 comm {k} [{lo},{hi})")
+            assert_close(f64(st[k][..., lo:hi]), r[k], TOL_F32, f"fp4 comm {k} [{lo},{hi})", scale=S[k])
     # at any size: at most 15 distinct sent values
     assert torch.unique(st["prev_local"][0, : 1 << 24]).numel() <= 15
     del st, state
@@ -377,44 +426,3 @@ def test_quadratic_forty_phases(variant, lr_div):
     np.testing.assert_allclose(losses, scaled, rtol=0.1)
     print(f"quadratic/{variant}/lr_div={lr_div}: loss {losses[0]:.4e} -> {losses[-1]:.4e}; worst window "
           f"loss deviation {worst_loss:.2e}, worst state error after {H * wl.phases} steps {worst_state:.2e}")
-
-
-@pytest.mark.parametrize("block,xcd,cap", [(0, 0, -1), (256, 0, 0), (64, 1, 3), (512, 1, 0), (256, 1, 1), (64, 0, 2)])
-def test_t550m_packed_state_eager_outer_step_per_call(block, xcd, cap):
-    """Config 3 through the packed-state entry point, in launch shapes the benchmark picks from."""
-    wl = W.WORKLOADS["t550m"]
-    M, n = wl.M, wl.n
-    st = W.outer_state(wl, n, device=DEV)
-    chunks = big_chunks(n) + [(d.STATE_TILE * 1000 - 100, d.STATE_TILE * 1000 + 100)]   # straddles a tile boundary
-    ref = [{k: f64(v[..., lo:hi]) for k, v in st.items()} for (lo, hi) in chunks]
-    state = torch.empty(d.packed_state_elems(M, n), device=DEV)
-    d.pack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
-                 prev_mean=st["prev_mean"])
-    for k in ("anchor", "vel", "prev_local", "prev_mean"):
-        st[k].zero_()
-    d.tune("block", block)
-    d.tune("xcd_remap", xcd)
-    d.tune("wg_per_cu", cap)
-    try:
-        d.outer_eager_packed(st["theta"], state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
-    finally:
-        d.tune("block", 0)
-        d.tune("xcd_remap", 0)
-        d.tune("wg_per_cu", -1)
-    d.unpack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
-                   prev_mean=st["prev_mean"])
-    torch.cuda.synchronize()
-    worst = 0.0
-    for r, (lo, hi) in zip(ref, chunks):
-        O.outer_eager(r["theta"], r["anchor"], r["vel"], r["prev_local"], r["prev_mean"],
-                      wl.outer_lr, wl.outer_momentum, True, True)
-        for k in r:
-            worst = max(worst, assert_close(f64(st[k][..., lo:hi]), r[k], TOL_F32, f"packed {k} [{lo},{hi})"))
-    assert torch.equal(st["theta"], st["anchor"])
-    s = st["prev_local"][0].double()
-    for m in range(1, M):
-        s += st["prev_local"][m].double()
-    assert torch.equal((s / M).float(), st["prev_mean"])     # M is a power of two: the division is exact
-    print(f"t550m packed, block={block} xcd_remap={xcd}: worst per-call error {worst:.2e}")
-    del st, state, s
-    torch.cuda.empty_cache()
