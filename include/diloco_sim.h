@@ -70,6 +70,23 @@ int diloco_sim_quadratic_loss(const float* theta, int M, int64_t n, int64_t stri
                               void* stream);
 
 /*
+ * diloco_sim_quadratic_loss for callers that cannot allocate and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The partial sums
+ * live in a 64 KB array that is part of the library's device image (8192 doubles, one copy per GPU
+ * the library runs on, held until the process ends); the call allocates nothing, on the device or
+ * through any library.  Same kernels, same order of summation: the result has the bits of
+ * diloco_sim_quadratic_loss.  n <= DILOCO_SIM_STATIC_LOSS_MAX_N, DILOCO_ERR_SHAPE beyond.  The
+ * first call on a GPU looks the array's address up (make that call outside a graph capture).
+ * All calls on one GPU share the array: calls that may overlap on one GPU (different streams
+ * without an ordering between them) race on it; calls on one stream are safe back to back, since
+ * every slot a call reads it has written itself.
+ */
+#define DILOCO_SIM_STATIC_LOSS_MAX_N ((int64_t)1 << 40)
+int diloco_sim_quadratic_loss_static(const float* theta, int M, int64_t n, int64_t stride,
+                                     const float* h, const float* theta_star, double* loss_out,
+                                     void* stream);
+
+/*
  * Launch shape of one call, for measurements.  The entry points of diloco.h choose their shape
  * themselves; the *_shaped variants below run the same call (same validation, same kernels, same
  * results bit for bit) in the shape the caller names, so that a harness can compare shapes

@@ -91,6 +91,7 @@ SIGNATURES = {
     "diloco_sim_loss_workspace": (_c_i64, [_c_i64]),
     "diloco_sim_quadratic_loss": (_c_int, [_c_ptr, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr,
                                            _c_i64, _c_ptr, _c_ptr]),
+    "diloco_sim_quadratic_loss_static": (_c_int, [_c_ptr, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr, _c_ptr]),
     "diloco_sim_stream_copy": (_c_int, [_c_ptr, _c_ptr, _c_i64, _c_ptr, _c_launch]),
     "diloco_tune": (_c_int, [ctypes.c_char_p, _c_int]),
     "diloco_tune_get": (_c_int, [ctypes.c_char_p]),
@@ -453,6 +454,14 @@ def sim_quadratic_loss(theta, h, theta_star, partials, loss_out, *, n=None, stre
     _check("diloco_sim_quadratic_loss", lib().diloco_sim_quadratic_loss(
         _ptr(theta), M, n, stride, _ptr(h), _ptr(theta_star), _ptr(partials), partials.numel(),
         _ptr(loss_out), _stream(stream)))
+
+
+def sim_quadratic_loss_static(theta, h, theta_star, loss_out, *, n=None, stream=None) -> None:
+    """sim_quadratic_loss without a workspace argument: the library's own static device array holds
+    the partial sums, nothing is allocated."""
+    a, M, n, stride = _loss_args("diloco_sim_quadratic_loss_static", theta, h, theta_star, loss_out, n)
+    _check("diloco_sim_quadratic_loss_static", lib().diloco_sim_quadratic_loss_static(
+        _ptr(theta), M, n, stride, _ptr(h), _ptr(theta_star), _ptr(loss_out), _stream(stream)))
 
 
 def sim_stream_copy(dst, src, *, stream=None, launch=None) -> None:

@@ -110,6 +110,28 @@ static int launch_rmw(float* base, int64_t stride, int64_t n, hipStream_t st, co
     return launch(stream_rmw_kernel<K>, dim3(g.blocks), dim3(shape.block), shape.lds, st, base, stride, n, g.per_xcd);
 }
 
+// Partial sums of the allocation-free loss: one copy of this array per GPU the library runs on,
+// held until the process ends.  In host code the name is only a handle for hipGetSymbolAddress;
+// the address kernels take is looked up once per device and kept.
+static __device__ __align__(256) double loss_scratch[kLossMaxBlocks];
+constexpr int kMaxDevices = 64;
+
+// Device address of the current GPU's loss_scratch (looked up on the first call on that GPU).
+static int static_loss_scratch(double** out) {
+    static std::mutex lock;
+    static double* ptrs[kMaxDevices];  // zero-initialised: not looked up yet
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DILOCO_ERR_LAUNCH;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(loss_scratch)) != hipSuccess || !p) return DILOCO_ERR_LAUNCH;
+        ptrs[dev] = static_cast<double*>(p);
+    }
+    *out = ptrs[dev];
+    return DILOCO_OK;
+}
+
 static int64_t loss_blocks(int64_t n) {
     int64_t b = (n + kLossBlock * 4 - 1) / (kLossBlock * 4);
     if (b < 1) b = 1;
@@ -140,6 +162,29 @@ extern "C" int diloco_sim_quadratic_loss(const float* theta, int M, int64_t n, i
     if (int e = check_alias(r, 5)) return e;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t nb = loss_blocks(n);
+    if (int e = launch(quadratic_loss_partial_kernel, dim3((unsigned)nb), dim3(kLossBlock), 0, st, theta, M, n,
+                       stride, h, theta_star, partials, 1.0 / M))
+        return e;
+    return launch(quadratic_loss_final_kernel, dim3(1), dim3(kLossBlock), 0, st, partials, nb, loss_out);
+}
+
+extern "C" int diloco_sim_quadratic_loss_static(const float* theta, int M, int64_t n, int64_t stride,
+                                                const float* h, const float* theta_star, double* loss_out,
+                                                void* stream) {
+    if (!theta || !h || !theta_star || !loss_out) return DILOCO_ERR_NULL;
+    if (int e = check_shape(M, n, stride)) return e;
+    if (n > DILOCO_SIM_STATIC_LOSS_MAX_N) return DILOCO_ERR_SHAPE;
+    if (!aligned_to(theta, 4) || !aligned_to(h, 4) || !aligned_to(theta_star, 4) || !aligned_to(loss_out, 8))
+        return DILOCO_ERR_ALIGN;
+    Range r[4] = {{theta, extent_bytes(M, n, stride, 4), false},
+                  {h, n * 4, false},
+                  {theta_star, n * 4, false},
+                  {loss_out, 8, true}};
+    if (int e = check_alias(r, 4)) return e;
+    double* partials = nullptr;
+    if (int e = static_loss_scratch(&partials)) return e;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t nb = loss_blocks(n);  // <= kLossMaxBlocks, the array's length; every slot read is written first
     if (int e = launch(quadratic_loss_partial_kernel, dim3((unsigned)nb), dim3(kLossBlock), 0, st, theta, M, n,
                        stride, h, theta_star, partials, 1.0 / M))
         return e;

@@ -217,6 +217,17 @@ def test_sim_validation_and_tuning(lib):
     assert lib.diloco_tune(b"generic_path", 3) == B.ERR_HYPER and lib.diloco_tune(b"xcd_remap", 2) == B.ERR_HYPER
 
 
+def test_static_loss_validation(lib):
+    """The allocation-free loss validates like the workspace one, and refuses sizes beyond its limit."""
+    def f(th=P[0], M=2, n=64, stride=64, h=P[1], star=P[2], out=P[3]):
+        return lib.diloco_sim_quadratic_loss_static(th, M, n, stride, h, star, out, None)
+    assert f(th=None) == B.ERR_NULL and f(out=None) == B.ERR_NULL
+    assert f(M=0) == B.ERR_SHAPE and f(n=-1) == B.ERR_SHAPE and f(stride=8) == B.ERR_SHAPE
+    assert f(M=1, n=(1 << 40) + 1, stride=(1 << 40) + 1) == B.ERR_SHAPE        # beyond the stated maximum
+    assert f(h=P[1] + 2) == B.ERR_ALIGN and f(out=P[3] + 4) == B.ERR_ALIGN
+    assert f(out=P[0] + 8) == B.ERR_ALIAS
+
+
 def test_explicit_launch_shapes_are_validated(lib):
     """The *_shaped entry points take the launch shape as an argument: NULL or a valid struct passes
     on to the ordinary validation, a field out of range is refused before anything else."""
