@@ -113,9 +113,12 @@ def adamw_scales(theta, m1, m2, g, t, lr, beta1, beta2, eps, weight_decay, g_sca
     g_scale: operand scale of the gradient itself when the call forms it (default: |g|, an input)."""
     sg = np.abs(g) if g_scale is None else g_scale
     s_m1 = beta1 * np.abs(m1) + (1.0 - beta1) * sg
-    s_m2 = beta2 * np.abs(m2) + (1.0 - beta2) * sg * sg    # all terms positive: the value itself
-    denom = np.sqrt(s_m2 / (1.0 - beta2 ** t)) + eps
-    s_upd = s_m1 / (1.0 - beta1 ** t) / denom
+    v = beta2 * np.abs(m2) + (1.0 - beta2) * g * g          # all terms positive: the value itself
+    s_m2 = beta2 * np.abs(m2) + (1.0 - beta2) * sg * sg     # = v unless the call forms g with cancellation
+    denom = np.sqrt(v / (1.0 - beta2 ** t)) + eps
+    # the step m1_hat / (sqrt(m2_hat) + eps) inherits m1's error relative to S_m1 and m2's relative to v
+    amp = np.where(v > 0.0, s_m2 / np.where(v > 0.0, v, 1.0), 1.0)
+    s_upd = s_m1 / (1.0 - beta1 ** t) / denom * amp
     return dict(m1=s_m1, m2=s_m2, theta=np.abs(theta) + lr * (s_upd + weight_decay * np.abs(theta)))
 
 
