@@ -117,8 +117,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="t550m")
-    ap.add_argument("--layout", choices=("packed", "rows"), default="packed",
-                    help="outer state: library-packed tiles (default) or caller rows [M][stride]")
+    ap.add_argument("--layout", choices=("pingpong", "packed", "rows"), default="pingpong",
+                    help="outer state: library-packed tiles read from one buffer and written to a second "
+                         "(default), the same tiles updated in place, or caller rows [M][stride]")
     ap.add_argument("--autotune", type=int, default=1,
                     help="pick workgroup size / XCD mapping per kernel before the warm-up (1) or keep defaults (0)")
     ap.add_argument("--pad", type=int, default=0, help="extra elements between replica rows")
@@ -193,7 +194,8 @@ def main():
     rows_all = timed(lambda: run_rows(shape_rows), max(5, args.steps // 2))
     rows_ms = sum(rows_all) / len(rows_all)
 
-    packed = args.layout == "packed"
+    packed = args.layout != "rows"
+    pingpong = args.layout == "pingpong"
     if packed:
         state = torch.empty(d.packed_state_elems(M, n), dtype=torch.float32, device=dev)
         d.pack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
@@ -203,9 +205,23 @@ def main():
             del st[k]
         torch.cuda.empty_cache()
 
-        def run_outer(sh=None, **kw):
+        def run_in_place(sh=None, **kw):
             d.outer_eager_packed(theta, state, n=n, launch=sh, **okw, **kw)
-        shape_outer = autotune(run_outer) if args.autotune else shape_default
+        shape_in_place = autotune(run_in_place) if args.autotune else shape_default
+        run_in_place(shape_in_place)
+        inplace_all = timed(lambda: run_in_place(shape_in_place), max(5, args.steps // 2))
+        if pingpong:
+            # the state is read from one buffer and written to the other; the two swap after every step
+            pair = [state, torch.empty_like(state)]
+            flip = [0]
+
+            def run_outer(sh=None, **kw):
+                d.outer_eager_pingpong(theta, pair[flip[0]], pair[1 - flip[0]], n=n, launch=sh, **okw, **kw)
+                flip[0] = 1 - flip[0]
+            run_outer()       # both buffers hold a full state from here on
+            shape_outer = autotune(run_outer) if args.autotune else shape_default
+        else:
+            run_outer, shape_outer = run_in_place, shape_in_place
     else:
         run_outer, shape_outer = run_rows, shape_rows
 
@@ -237,7 +253,7 @@ def main():
     outer_ms = sum(outer_all) / args.steps
     if packed:
         chk = torch.empty((M, 4096), device=dev)
-        d.unpack_state(state, M, 4096, anchor=chk)
+        d.unpack_state(pair[flip[0]] if pingpong else state, M, 4096, anchor=chk)
         assert torch.isfinite(chk).all()
     else:
         assert torch.isfinite(st["anchor"][:, :1024]).all()
@@ -251,7 +267,7 @@ def main():
         def run_fragments():
             for off, cnt in frs:
                 d.outer_eager_packed(theta[:, off:off + cnt], d.packed_window(state, M, off), n=cnt,
-                                     launch=shape_outer, **okw)
+                                     launch=shape_in_place, **okw)
         run_fragments()
         fms = timed(run_fragments, 5)[2]
         extra["outer_step_by_fragments"] = {"fragments": len(frs), "ms": fms,
@@ -380,25 +396,31 @@ def main():
         "outer_step_rows_layout": {"ms": rows_ms, "GBps": outer_bytes / (rows_ms * 1e-3) / 1e9,
                                    "frac_of_peak": outer_bytes / (rows_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                    "per_launch": rows_spread, "launch": shape_json(shape_rows)},
+        **({"outer_step_packed_in_place": dict(rates(inplace_all, outer_bytes), launch=shape_json(shape_in_place))}
+           if packed else {}),
         "inner_step": {"ms": inner_ms, "worker_params_per_s": M * n / (inner_ms * 1e-3),
                        "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS, "per_step": inner_spread},
         **extra,
         "copy_ceiling_GBps": copy_gbps,
         "stream_rmw_ceiling": None if rmw_gbps is None else {"K": K, "GBps": rmw_gbps,
                                                              "launch": shape_json(shape_rmw)},
-        "roofline": {"bound": "hbm", "kernel": "outer_eager_reg_kernel<%d, %s, eager, %s>" % (
-                         M, "bf16" if bf16 else "float", "TiledState" if packed else "RowState"), "achieved": outer_gbps,
+        "roofline": {"bound": "hbm", "kernel": "outer_eager_reg_kernel<%d, %s, eager, %s>%s" % (
+                         M, "bf16" if bf16 else "float", "TiledState" if packed else "RowState",
+                         " (state read from one buffer, written to another)" if pingpong else ""),
+                     "achieved": outer_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": outer_gbps / HBM_PEAK_GBPS,
                      "frac_min_median_max": [outer_spread["frac_of_peak"][k] for k in ("max", "median", "min")],
                      "frac_of_copy": outer_gbps / copy_gbps,
                      "frac_of_stream_rmw": None if rmw_gbps is None else outer_gbps / rmw_gbps,
-                     "traffic": stored_traffic(wl.name, args.layout)},
+                     "traffic": stored_traffic(wl.name, "packed" if packed else "rows")},
     }
     if result["roofline"]["traffic"]:   # counter bytes over this run's time: the rate the counters imply
         result["roofline"]["traffic_GBps"] = result["roofline"]["traffic"] / (outer_ms * 1e-3) / 1e9
     del st, ad, theta, m1, m2, grad
     if packed:
         del state
+        if pingpong:
+            del pair
     torch.cuda.empty_cache()
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample)

@@ -216,6 +216,23 @@ int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, int M, int6
                               double outer_lr, double outer_momentum, int nesterov,
                               int variant, int apply_update, void* stream);
 
+/*
+ * The same step (Algorithm 3 lines 7-12 / Algorithm 2 lines 7-11) reading the packed outer state
+ * from state_in and writing the new one to state_out, two separate buffers of
+ * diloco_packed_state_elems(M, n) floats that the caller swaps between boundaries.  On this chip
+ * a sweep that reads one buffer and writes another streams 1-2 % faster than the same sweep in
+ * place; the price is a second state buffer (with 288 GB of HBM the M = 8, 617M-parameter
+ * configuration still fits twice over).  Results are bit-identical to
+ * diloco_outer_eager_packed.  Every stream of state_out is written (at the first boundary,
+ * apply_update == 0, the velocities are copied across), except the mean stream under
+ * DILOCO_STATE_NO_MEAN, which no flagged call reads.  theta is updated in place.
+ * state_in == state_out or overlapping buffers: DILOCO_ERR_ALIAS.
+ */
+int diloco_outer_eager_pingpong(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                int64_t stride, const float* state_in, float* state_out,
+                                double outer_lr, double outer_momentum, int nesterov,
+                                int variant, int apply_update, void* stream);
+
 /* theta_m <- outer parameters of replica m, read from the packed state. */
 int diloco_reset_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
                         const float* state, void* stream);

@@ -131,6 +131,11 @@ int diloco_outer_eager_packed_shaped(void* theta, diloco_dtype theta_dtype, int 
                                      double outer_lr, double outer_momentum, int nesterov,
                                      int variant, int apply_update, void* stream,
                                      const diloco_launch* launch);
+int diloco_outer_eager_pingpong_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                       int64_t stride, const float* state_in, float* state_out,
+                                       double outer_lr, double outer_momentum, int nesterov,
+                                       int variant, int apply_update, void* stream,
+                                       const diloco_launch* launch);
 
 /*
  * Measurement aid: dst[i] <- src[i] for n fp32 elements with the same 128-bit
@@ -151,6 +156,18 @@ int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, void* stream
  */
 int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stride, void* stream,
                           const diloco_launch* launch);
+
+/*
+ * The same sweep with its two halves apart, to tell which of them the memory system limits:
+ * DILOCO_SIM_SWEEP_RMW is diloco_sim_stream_rmw; DILOCO_SIM_SWEEP_READ only reads the K rows
+ * (moves 4Kn bytes, writes nothing); DILOCO_SIM_SWEEP_WRITE only writes them, every element set
+ * to `fill` (moves 4Kn bytes).  Other modes: DILOCO_ERR_DTYPE.  Arguments as above.
+ */
+#define DILOCO_SIM_SWEEP_RMW 0
+#define DILOCO_SIM_SWEEP_READ 1
+#define DILOCO_SIM_SWEEP_WRITE 2
+int diloco_sim_stream_sweep(float* base, int K, int64_t n, int64_t stride, int mode, float fill,
+                            void* stream, const diloco_launch* launch);
 
 /*
  * The launch shape that calls WITHOUT an explicit shape use on the calling thread (test aid): the

@@ -77,6 +77,10 @@ SIGNATURES = {
     "diloco_unpack_state": (_c_int, [_c_ptr, _c_int, _c_i64, _c_ptr, _c_ptr, _c_ptr, _c_i64, _c_ptr, _c_ptr]),
     "diloco_outer_eager_packed": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_dbl, _c_dbl,
                                            _c_int, _c_int, _c_int, _c_ptr]),
+    "diloco_outer_eager_pingpong": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_dbl, _c_dbl,
+                                             _c_int, _c_int, _c_int, _c_ptr]),
+    "diloco_outer_eager_pingpong_shaped": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_dbl,
+                                                    _c_dbl, _c_int, _c_int, _c_int, _c_ptr, _c_launch]),
     "diloco_reset_packed": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr]),
     "diloco_stream_offset": (_c_i64, [_c_i64, _c_int, _c_int]),
     "diloco_stream_due": (_c_int, [_c_i64, _c_i64, _c_int, _c_int]),
@@ -88,6 +92,7 @@ SIGNATURES = {
                                             _c_ptr, _c_dbl, ctypes.c_uint64, _c_i64, _c_dbl, _c_dbl,
                                             _c_dbl, _c_dbl, _c_dbl, _c_i64, _c_int, _c_ptr]),
     "diloco_sim_stream_rmw": (_c_int, [_c_ptr, _c_int, _c_i64, _c_i64, _c_ptr, _c_launch]),
+    "diloco_sim_stream_sweep": (_c_int, [_c_ptr, _c_int, _c_i64, _c_i64, _c_int, ctypes.c_float, _c_ptr, _c_launch]),
     "diloco_sim_loss_workspace": (_c_i64, [_c_i64]),
     "diloco_sim_quadratic_loss": (_c_int, [_c_ptr, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_ptr,
                                            _c_i64, _c_ptr, _c_ptr]),
@@ -354,6 +359,22 @@ def outer_eager_packed(theta, state, *, n=None, outer_lr, outer_momentum, nester
         _check("diloco_outer_eager_packed_shaped", lib().diloco_outer_eager_packed_shaped(*args, _launch(launch)))
 
 
+def outer_eager_pingpong(theta, state_in, state_out, *, n=None, outer_lr, outer_momentum, nesterov=True,
+                         variant=EAGER, apply_update=True, stream=None, launch=None) -> None:
+    """diloco_outer_eager_pingpong: the packed step reading state_in and writing state_out (two buffers
+    of packed_state_elems(M, n) floats that the caller swaps between boundaries)."""
+    M, n = _shape_of(theta, n)
+    a = _packed_args("diloco_outer_eager_pingpong", state_in, M, n)
+    a.vec(state_out, "state_out", packed_state_elems(M, n))
+    stride = a.rows(theta, "theta", M, n, _PARAM_DTYPES)
+    args = (_ptr(theta), _dtype_code(theta), M, n, stride, _ptr(state_in), _ptr(state_out), outer_lr, outer_momentum,
+            int(nesterov), int(variant), int(apply_update), _stream(stream))
+    if launch is None:
+        _check("diloco_outer_eager_pingpong", lib().diloco_outer_eager_pingpong(*args))
+    else:
+        _check("diloco_outer_eager_pingpong_shaped", lib().diloco_outer_eager_pingpong_shaped(*args, _launch(launch)))
+
+
 def reset_packed(theta, state, *, n=None, stream=None) -> None:
     M, n = _shape_of(theta, n)
     a = _packed_args("diloco_reset_packed", state, M, n)
@@ -479,6 +500,19 @@ def sim_stream_rmw(rows, *, n=None, stream=None, launch=None) -> None:
     stride = a.rows(rows, "rows", K, min(n, rows.shape[1]))
     _check("diloco_sim_stream_rmw", lib().diloco_sim_stream_rmw(_ptr(rows), K, n, stride, _stream(stream),
                                                                 _launch(launch)))
+
+
+SWEEP_RMW, SWEEP_READ, SWEEP_WRITE = 0, 1, 2
+
+
+def sim_stream_sweep(rows, mode, *, n=None, fill=0.0, stream=None, launch=None) -> None:
+    """sim_stream_rmw with its halves apart: SWEEP_RMW, SWEEP_READ (nothing written) or SWEEP_WRITE
+    (every element set to `fill`)."""
+    K, n = _shape_of(rows, n)
+    a = _Args("diloco_sim_stream_sweep")
+    stride = a.rows(rows, "rows", K, min(n, rows.shape[1]))
+    _check("diloco_sim_stream_sweep", lib().diloco_sim_stream_sweep(
+        _ptr(rows), K, n, stride, int(mode), float(fill), _stream(stream), _launch(launch)))
 
 
 def tune(key: str, value: int) -> None:

@@ -16,6 +16,10 @@
 //               the kernel touches them (a_0..a_{M-1}, D, u_0, P_0, u_1, P_1, ...), so a
 //               wavefront's 3M+1 state accesses fall into one or two 2 MB pages instead of
 //               3M+1 pages that are gigabytes apart (fewer address-translation misses).
+// Every kernel takes two views: `sv`, where the state is read, and `so`, where the new state is
+// written.  They are the same buffer for the in-place entry points; the ping-pong entry point
+// passes two packed buffers (a read-modify-write in place streams 1-2 % slower on this chip
+// than the same sweep reading one buffer and writing another).
 #include "common.hpp"
 
 namespace diloco {
@@ -86,6 +90,7 @@ struct RowState {
     __device__ __forceinline__ float* u(int m, int64_t i) const { return vel + m * ss + i; }
     __device__ __forceinline__ float* p(int m, int64_t i) const { return P + m * ss + i; }
     __device__ __forceinline__ float* d(int64_t i) const { return D + i; }
+    __device__ __forceinline__ bool same_as(const RowState& o) const { return anchor == o.anchor; }
 };
 
 struct TiledState {
@@ -98,6 +103,7 @@ struct TiledState {
     __device__ __forceinline__ float* d(int64_t i) const { return at(M, i); }
     __device__ __forceinline__ float* u(int m, int64_t i) const { return at(M + 1 + 2 * m, i); }
     __device__ __forceinline__ float* p(int m, int64_t i) const { return at(M + 2 + 2 * m, i); }
+    __device__ __forceinline__ bool same_as(const TiledState& o) const { return base == o.base; }
 };
 
 // OuterOpt on one value (or 4): u <- mu u + G ; a <- a - (c_g G + c_u u).
@@ -117,7 +123,7 @@ __device__ __forceinline__ T eager_gradient(T d, T p, T Dold, const OuterScalars
 // theta_m and a_m).  Serves misaligned buffers and the ragged tail of the vector kernels;
 // same arithmetic, same order.
 template <typename TT, int MODE, typename SV>
-__device__ void eager_element(TT* theta, SV sv, int M, int64_t stride, int64_t i,
+__device__ void eager_element(TT* theta, SV sv, SV so, int M, int64_t stride, int64_t i,
                               const OuterScalars& sc) {
     double s = 0.0;
     for (int m = 0; m < M; ++m) {
@@ -139,47 +145,48 @@ __device__ void eager_element(TT* theta, SV sv, int M, int64_t stride, int64_t i
         float th = load1(theta + m * stride + i);
         float d = a - th;
         if (MODE == MODE_RECORD) {
-            store1(sv.a(m, i), th);
+            store1(so.a(m, i), th);
+            if (!sv.same_as(so)) store1(so.u(m, i), load1(sv.u(m, i)));  // the velocity moves along unchanged
         } else {
             float u = load1(sv.u(m, i));
             float G = Dold;
             if (MODE == MODE_EAGER) G = eager_gradient(d, load1(sv.p(m, i)), Dold, sc);
             outer_opt(a, u, G, sc);
             store1(theta + m * stride + i, a);
-            store1(sv.a(m, i), a);
-            store1(sv.u(m, i), u);
+            store1(so.a(m, i), a);
+            store1(so.u(m, i), u);
         }
-        store1(sv.p(m, i), sent(d, sc));
+        store1(so.p(m, i), sent(d, sc));
     }
-    if (!sc.no_mean) store1(sv.d(i), dbar);
+    if (!sc.no_mean) store1(so.d(i), dbar);
 }
 
 template <typename TT, int MODE, typename SV>
-__global__ __launch_bounds__(kMaxBlock) void outer_eager_scalar_kernel(TT* theta, SV sv, int M, int64_t n,
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_scalar_kernel(TT* theta, SV sv, SV so, int M, int64_t n,
                                                                        int64_t stride, OuterScalars sc,
                                                                        int64_t per_xcd) {
     int64_t i = logical_block(per_xcd) * blockDim.x + threadIdx.x;
-    if (i < n) eager_element<TT, MODE, SV>(theta, sv, M, stride, i, sc);
+    if (i < n) eager_element<TT, MODE, SV>(theta, sv, so, M, stride, i, sc);
 }
 
 // Tail of a vector kernel: the thread right after the last full vector sweeps n % 4 elements.
 template <typename TT, int MODE, typename SV>
-__device__ __forceinline__ void eager_tail(TT* theta, SV sv, int M, int64_t n, int64_t stride,
+__device__ __forceinline__ void eager_tail(TT* theta, SV sv, SV so, int M, int64_t n, int64_t stride,
                                            const OuterScalars& sc) {
-    for (int64_t i = n & ~(int64_t)3; i < n; ++i) eager_element<TT, MODE, SV>(theta, sv, M, stride, i, sc);
+    for (int64_t i = n & ~(int64_t)3; i < n; ++i) eager_element<TT, MODE, SV>(theta, sv, so, M, stride, i, sc);
 }
 
 // ------------------------------------------------------------------ register path
 // M known at compile time: a_m and Delta_m of all replicas stay in registers between the
 // reduction and the update (2*M*4 VGPRs), nothing is read twice.
 template <int M, typename TT, int MODE, typename SV>
-__global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restrict__ theta, SV sv, int64_t n,
+__global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restrict__ theta, SV sv, SV so, int64_t n,
                                                                     int64_t stride, OuterScalars sc,
                                                                     int64_t per_xcd) {
     const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     const int64_t nvec = n >> 2;
     if (v >= nvec) {
-        if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, M, n, stride, sc);
+        if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, so, M, n, stride, sc);
         return;
     }
     const int64_t i = v << 2;
@@ -230,11 +237,19 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
     // replica this measured between equal and 6 % faster on t550m, depending on where the
     // buffers happen to lie in memory; it was never slower.
     if (MODE == MODE_RECORD) {
+        const bool carry = !sv.same_as(so);  // another buffer: the velocity moves along unchanged
+        if (carry) {
 #pragma unroll
-        for (int m = 0; m < M; ++m) store4(sv.a(m, i), th[m]);
-        if (!sc.no_mean) store4(sv.d(i), dbar);
+            for (int m = 0; m < M; ++m) u[m] = load4(sv.u(m, i));
+        }
 #pragma unroll
-        for (int m = 0; m < M; ++m) store4(sv.p(m, i), sent(d[m], sc));
+        for (int m = 0; m < M; ++m) store4(so.a(m, i), th[m]);
+        if (!sc.no_mean) store4(so.d(i), dbar);
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            if (carry) store4(so.u(m, i), u[m]);
+            store4(so.p(m, i), sent(d[m], sc));
+        }
         return;
     }
 #pragma unroll
@@ -246,12 +261,12 @@ __global__ __launch_bounds__(kMaxBlock) void outer_eager_reg_kernel(TT* __restri
 #pragma unroll
     for (int m = 0; m < M; ++m) store4(theta + m * stride + i, a[m]);
 #pragma unroll
-    for (int m = 0; m < M; ++m) store4(sv.a(m, i), a[m]);
-    if (!sc.no_mean) store4(sv.d(i), dbar);
+    for (int m = 0; m < M; ++m) store4(so.a(m, i), a[m]);
+    if (!sc.no_mean) store4(so.d(i), dbar);
 #pragma unroll
     for (int m = 0; m < M; ++m) {
-        store4(sv.u(m, i), u[m]);
-        store4(sv.p(m, i), sent(d[m], sc));
+        store4(so.u(m, i), u[m]);
+        store4(so.p(m, i), sent(d[m], sc));
     }
 }
 
@@ -305,9 +320,9 @@ __device__ __forceinline__ void group_reduce(const TT* __restrict__ theta, const
 // Second pass over one group.  STAGE: a_m (theta_m) and Delta_m (and, NOMEAN, the previous local
 // outer gradient) come back from LDS; otherwise they are read again.
 template <typename TT, int MODE, typename SV, bool FULL, bool STAGE, bool NOMEAN>
-__device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& sv, int m0, int cnt, int64_t i,
-                                             int64_t stride, const OuterScalars& sc, const f4* stage, int tid,
-                                             f4 Dold) {
+__device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& sv, const SV& so, int m0, int cnt,
+                                             int64_t i, int64_t stride, const OuterScalars& sc, const f4* stage,
+                                             int tid, f4 Dold) {
     constexpr int kSlots = NOMEAN ? 3 : 2;
     f4 a[kGroup], d[kGroup], u[kGroup], p[kGroup];
 #pragma unroll
@@ -317,7 +332,7 @@ __device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& s
                 a[j] = load4(sv.a(m0 + j, i));
                 d[j] = load4(theta + (m0 + j) * stride + i);  // theta for now
             }
-            if (MODE != MODE_RECORD) u[j] = load4(sv.u(m0 + j, i));
+            if (MODE != MODE_RECORD || !sv.same_as(so)) u[j] = load4(sv.u(m0 + j, i));
             if (MODE == MODE_EAGER && !(STAGE && NOMEAN)) p[j] = load4(sv.p(m0 + j, i));
         }
 #pragma unroll
@@ -345,12 +360,12 @@ __device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& s
     }
 #pragma unroll
     for (int j = 0; j < kGroup; ++j)
-        if (FULL || j < cnt) store4(sv.a(m0 + j, i), a[j]);
+        if (FULL || j < cnt) store4(so.a(m0 + j, i), a[j]);
 #pragma unroll
     for (int j = 0; j < kGroup; ++j)
         if (FULL || j < cnt) {
-            if (MODE != MODE_RECORD) store4(sv.u(m0 + j, i), u[j]);
-            store4(sv.p(m0 + j, i), sent(d[j], sc));
+            if (MODE != MODE_RECORD || !sv.same_as(so)) store4(so.u(m0 + j, i), u[j]);  // recording: moved along
+            store4(so.p(m0 + j, i), sent(d[j], sc));
         }
 }
 
@@ -362,15 +377,15 @@ __device__ __forceinline__ void group_update(TT* __restrict__ theta, const SV& s
 // previous mean is the fp64 sum of the previous locals in replica order, rounded once, and the
 // mean stream is neither read nor written (recording without a stored mean only skips the store).
 template <typename TT, int MODE, typename SV, bool NOMEAN>
-__global__ __launch_bounds__(64) void outer_eager_grouped_kernel(TT* __restrict__ theta, SV sv, int M, int staged,
-                                                                 int64_t n, int64_t stride, OuterScalars sc,
-                                                                 int64_t per_xcd) {
+__global__ __launch_bounds__(64) void outer_eager_grouped_kernel(TT* __restrict__ theta, SV sv, SV so, int M,
+                                                                 int staged, int64_t n, int64_t stride,
+                                                                 OuterScalars sc, int64_t per_xcd) {
     static_assert(!NOMEAN || MODE == MODE_EAGER, "only the eager combination forms the previous mean itself");
     extern __shared__ f4 stage[];  // [staged][2 or 3][64]
     const int64_t v = logical_block(per_xcd) * 64 + threadIdx.x;
     const int64_t nvec = n >> 2;
     if (v >= nvec) {
-        if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, M, n, stride, sc);
+        if (v == nvec) eager_tail<TT, MODE, SV>(theta, sv, so, M, n, stride, sc);
         return;
     }
     const int64_t i = v << 2;
@@ -399,17 +414,17 @@ __global__ __launch_bounds__(64) void outer_eager_grouped_kernel(TT* __restrict_
         Dold = load4(sv.d(i));
     for (m0 = 0; m0 + kGroup <= M; m0 += kGroup) {
         if (m0 < staged)
-            group_update<TT, MODE, SV, true, true, NOMEAN>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
+            group_update<TT, MODE, SV, true, true, NOMEAN>(theta, sv, so, m0, kGroup, i, stride, sc, stage, tid, Dold);
         else
-            group_update<TT, MODE, SV, true, false, NOMEAN>(theta, sv, m0, kGroup, i, stride, sc, stage, tid, Dold);
+            group_update<TT, MODE, SV, true, false, NOMEAN>(theta, sv, so, m0, kGroup, i, stride, sc, stage, tid, Dold);
     }
     if (m0 < M) {
         if (m0 < staged)
-            group_update<TT, MODE, SV, false, true, NOMEAN>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
+            group_update<TT, MODE, SV, false, true, NOMEAN>(theta, sv, so, m0, M - m0, i, stride, sc, stage, tid, Dold);
         else
-            group_update<TT, MODE, SV, false, false, NOMEAN>(theta, sv, m0, M - m0, i, stride, sc, stage, tid, Dold);
+            group_update<TT, MODE, SV, false, false, NOMEAN>(theta, sv, so, m0, M - m0, i, stride, sc, stage, tid, Dold);
     }
-    if (!sc.no_mean) store4(sv.d(i), dbar);
+    if (!sc.no_mean) store4(so.d(i), dbar);
 }
 
 // ------------------------------------------------------------------ standard DiLoCo
@@ -613,7 +628,7 @@ static OuterScalars make_scalars(int M, double lr, double mu, int nesterov) {
 }
 
 template <typename TT, int MODE, typename SV>
-static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, const OuterScalars& sc,
+static int launch_eager(TT* theta, SV sv, SV so, int M, int64_t n, int64_t stride, const OuterScalars& sc,
                         bool vec_ok, hipStream_t st, const Tuning& t) {
     // a wavefront of the vector kernels loads theta_m, a_m, u_m, P_m of every replica and D: 16 B a lane each
     const Shape shape =
@@ -622,8 +637,8 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
     if (!vec_ok) {
         if (!grid_fits(n, block)) return DILOCO_ERR_SHAPE;
         Grid g = make_grid(t, n, block);
-        return launch(outer_eager_scalar_kernel<TT, MODE, SV>, dim3(g.blocks), dim3(block), 0, st, theta, sv, M, n,
-                      stride, sc, g.per_xcd);
+        return launch(outer_eager_scalar_kernel<TT, MODE, SV>, dim3(g.blocks), dim3(block), 0, st, theta, sv, so, M,
+                      n, stride, sc, g.per_xcd);
     }
     const int64_t threads = (n >> 2) + ((n & 3) ? 1 : 0);
     if (!grid_fits(threads, 64)) return DILOCO_ERR_SHAPE;
@@ -632,7 +647,7 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
         Grid g = make_grid(t, threads, block);                                                          \
         if (!grant_lds(&outer_eager_reg_kernel<MM, TT, MODE, SV>, shape.lds)) return DILOCO_ERR_LAUNCH; \
         return launch(outer_eager_reg_kernel<MM, TT, MODE, SV>, dim3(g.blocks), dim3(block), shape.lds, st, theta,  \
-                      sv, n, stride, sc, g.per_xcd);                                                    \
+                      sv, so, n, stride, sc, g.per_xcd);                                                \
     }
     // a forced generic path also replaces the register kernels
     switch (t.generic_path ? 0 : M) {
@@ -669,21 +684,21 @@ static int launch_eager(TT* theta, SV sv, int M, int64_t n, int64_t stride, cons
         // only instantiated for the eager mode (the others never form the previous mean)
         auto kernel = outer_eager_grouped_kernel<TT, kNoMeanKernel ? MODE : MODE_EAGER, SV, true>;
         if (!grant_lds(kernel, lds)) return DILOCO_ERR_LAUNCH;
-        return launch(kernel, dim3(g.blocks), dim3(64), lds, st, theta, sv, M, staged, n, stride, sc, g.per_xcd);
+        return launch(kernel, dim3(g.blocks), dim3(64), lds, st, theta, sv, so, M, staged, n, stride, sc, g.per_xcd);
     }
     if (!grant_lds(&outer_eager_grouped_kernel<TT, MODE, SV, false>, lds)) return DILOCO_ERR_LAUNCH;
-    return launch(outer_eager_grouped_kernel<TT, MODE, SV, false>, dim3(g.blocks), dim3(64), lds, st, theta, sv, M,
-                  staged, n, stride, sc, g.per_xcd);
+    return launch(outer_eager_grouped_kernel<TT, MODE, SV, false>, dim3(g.blocks), dim3(64), lds, st, theta, sv, so,
+                  M, staged, n, stride, sc, g.per_xcd);
 }
 
 template <typename TT, typename SV>
-static int dispatch_eager(void* theta, SV sv, int M, int64_t n, int64_t stride, const OuterScalars& sc,
+static int dispatch_eager(void* theta, SV sv, SV so, int M, int64_t n, int64_t stride, const OuterScalars& sc,
                           bool vec_ok, int mode, hipStream_t st, const Tuning& t) {
     TT* th = static_cast<TT*>(theta);
     switch (mode) {
-        case MODE_RECORD: return launch_eager<TT, MODE_RECORD, SV>(th, sv, M, n, stride, sc, vec_ok, st, t);
-        case MODE_EAGER: return launch_eager<TT, MODE_EAGER, SV>(th, sv, M, n, stride, sc, vec_ok, st, t);
-        default: return launch_eager<TT, MODE_DELAYED, SV>(th, sv, M, n, stride, sc, vec_ok, st, t);
+        case MODE_RECORD: return launch_eager<TT, MODE_RECORD, SV>(th, sv, so, M, n, stride, sc, vec_ok, st, t);
+        case MODE_EAGER: return launch_eager<TT, MODE_EAGER, SV>(th, sv, so, M, n, stride, sc, vec_ok, st, t);
+        default: return launch_eager<TT, MODE_DELAYED, SV>(th, sv, so, M, n, stride, sc, vec_ok, st, t);
     }
 }
 
@@ -744,14 +759,16 @@ static int outer_eager_impl(void* theta, int theta_dtype, int M, int64_t n, int6
     const RowState sv{anchor, vel, prev_local, prev_mean, state_stride};
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int mode = mode_of(v.base, apply_update);
-    if (theta_dtype == DILOCO_F32) return dispatch_eager<float, RowState>(theta, sv, M, n, stride, sc, vec_ok, mode, st, t);
-    return dispatch_eager<__bf16, RowState>(theta, sv, M, n, stride, sc, vec_ok, mode, st, t);
+    if (theta_dtype == DILOCO_F32)
+        return dispatch_eager<float, RowState>(theta, sv, sv, M, n, stride, sc, vec_ok, mode, st, t);
+    return dispatch_eager<__bf16, RowState>(theta, sv, sv, M, n, stride, sc, vec_ok, mode, st, t);
 }
 
+// state_out == state: in place.  Otherwise the state is read from `state` and written to state_out.
 static int outer_eager_packed_impl(void* theta, int theta_dtype, int M, int64_t n, int64_t stride, float* state,
-                                   double outer_lr, double outer_momentum, int nesterov, int variant,
-                                   int apply_update, void* stream, const Tuning& t) {
-    if (!theta || !state) return DILOCO_ERR_NULL;
+                                   float* state_out, double outer_lr, double outer_momentum, int nesterov,
+                                   int variant, int apply_update, void* stream, const Tuning& t) {
+    if (!theta || !state || !state_out) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
     Variant v;
     if (int e = parse_variant(variant, v)) return e;
@@ -759,18 +776,21 @@ static int outer_eager_packed_impl(void* theta, int theta_dtype, int M, int64_t 
     if (n > ((int64_t)1 << 40)) return DILOCO_ERR_SHAPE;
     if (!is_finite(outer_lr) || !in_unit(outer_momentum)) return DILOCO_ERR_HYPER;
     const int es = elem_size(theta_dtype);
-    if (!aligned_to(theta, es) || !aligned_to(state, 16)) return DILOCO_ERR_ALIGN;
-    Range r[2] = {{theta, extent_bytes(M, n, stride, es), true}, {state, packed_elems(M, n) * 4, true}};
-    if (int e = check_alias(r, 2)) return e;
+    if (!aligned_to(theta, es) || !aligned_to(state, 16) || !aligned_to(state_out, 16)) return DILOCO_ERR_ALIGN;
+    const bool in_place = state_out == state;
+    Range r[3] = {{theta, extent_bytes(M, n, stride, es), true},
+                  {state, packed_elems(M, n) * 4, in_place},
+                  {in_place ? nullptr : state_out, packed_elems(M, n) * 4, true}};
+    if (int e = check_alias(r, 3)) return e;
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
     const OuterScalars sc = eager_scalars(M, outer_lr, outer_momentum, nesterov, v);
-    const TiledState sv{state, (int64_t)M};
+    const TiledState sv{state, (int64_t)M}, so{state_out, (int64_t)M};
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int mode = mode_of(v.base, apply_update);
     if (theta_dtype == DILOCO_F32)
-        return dispatch_eager<float, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode, st, t);
-    return dispatch_eager<__bf16, TiledState>(theta, sv, M, n, stride, sc, vec_ok, mode, st, t);
+        return dispatch_eager<float, TiledState>(theta, sv, so, M, n, stride, sc, vec_ok, mode, st, t);
+    return dispatch_eager<__bf16, TiledState>(theta, sv, so, M, n, stride, sc, vec_ok, mode, st, t);
 }
 
 }  // namespace diloco
@@ -806,8 +826,29 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
                                          int64_t stride, float* state, double outer_lr,
                                          double outer_momentum, int nesterov, int variant,
                                          int apply_update, void* stream) {
-    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, outer_lr, outer_momentum, nesterov,
-                                   variant, apply_update, stream, tuning());
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, state, outer_lr, outer_momentum,
+                                   nesterov, variant, apply_update, stream, tuning());
+}
+
+extern "C" int diloco_outer_eager_pingpong(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                           int64_t stride, const float* state_in, float* state_out,
+                                           double outer_lr, double outer_momentum, int nesterov, int variant,
+                                           int apply_update, void* stream) {
+    if (state_in == state_out && state_in) return DILOCO_ERR_ALIAS;
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, const_cast<float*>(state_in), state_out,
+                                   outer_lr, outer_momentum, nesterov, variant, apply_update, stream, tuning());
+}
+
+extern "C" int diloco_outer_eager_pingpong_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                                  int64_t stride, const float* state_in, float* state_out,
+                                                  double outer_lr, double outer_momentum, int nesterov,
+                                                  int variant, int apply_update, void* stream,
+                                                  const diloco_launch* launch) {
+    Tuning t;
+    if (!resolve_launch(launch, t)) return DILOCO_ERR_HYPER;
+    if (state_in == state_out && state_in) return DILOCO_ERR_ALIAS;
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, const_cast<float*>(state_in), state_out,
+                                   outer_lr, outer_momentum, nesterov, variant, apply_update, stream, t);
 }
 
 extern "C" int diloco_outer_eager_packed_shaped(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
@@ -816,8 +857,8 @@ extern "C" int diloco_outer_eager_packed_shaped(void* theta, diloco_dtype theta_
                                                 int apply_update, void* stream, const diloco_launch* launch) {
     Tuning t;
     if (!resolve_launch(launch, t)) return DILOCO_ERR_HYPER;
-    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, outer_lr, outer_momentum, nesterov,
-                                   variant, apply_update, stream, t);
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, state, outer_lr, outer_momentum,
+                                   nesterov, variant, apply_update, stream, t);
 }
 
 // rows <-> tiled.  Any of anchor / vel / prev_local / prev_mean may be NULL (skipped).

@@ -88,26 +88,49 @@ __global__ __launch_bounds__(kMaxBlock) void stream_copy_kernel(float* __restric
 // In-place sweep over K rows `stride` apart: every lane loads its 16 bytes of all K rows, then
 // stores them back unchanged.  No arithmetic: what is left is the memory system's rate for a
 // read-modify-write over K separated streams, the access pattern of the outer steps.
-template <int K>
-__global__ __launch_bounds__(kMaxBlock) void stream_rmw_kernel(float* __restrict__ base, int64_t stride,
-                                                               int64_t n, int64_t per_xcd) {
+// MODE 0: read every row's piece, write it back.  1: read only (the values are summed and the sum
+// compared with a value no input produces, so that the loads cannot be dropped; nothing is
+// written).  2: write only (every piece is filled with `fill`).
+template <int K, int MODE>
+__global__ __launch_bounds__(kMaxBlock) void stream_sweep_kernel(float* __restrict__ base, int64_t stride,
+                                                                 int64_t n, float fill, int64_t per_xcd) {
     const int64_t v = logical_block(per_xcd) * blockDim.x + threadIdx.x;
     if (v >= (n >> 2)) return;
     f4 x[K];
+    if (MODE != 2) {
 #pragma unroll
-    for (int k = 0; k < K; ++k) x[k] = load4(base + k * stride + (v << 2));
+        for (int k = 0; k < K; ++k) x[k] = load4(base + k * stride + (v << 2));
+    } else {
+#pragma unroll
+        for (int k = 0; k < K; ++k) x[k] = f4{fill, fill, fill, fill};
+    }
+    if (MODE == 1) {
+        float acc = 0.f;
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc += (x[k].x + x[k].y) + (x[k].z + x[k].w);
+        if (acc != fill) return;  // `fill` is a NaN for this mode: never equal, the store below never happens
+    }
 #pragma unroll
     for (int k = 0; k < K; ++k) store4(base + k * stride + (v << 2), x[k]);
 }
 
-template <int K>
-static int launch_rmw(float* base, int64_t stride, int64_t n, hipStream_t st, const Tuning& t) {
+template <int K, int MODE>
+static int launch_sweep_mode(float* base, int64_t stride, int64_t n, float fill, hipStream_t st, const Tuning& t) {
+    // bytes a wavefront has in flight: its K loads, or (write only) its K stores
     const Shape shape = launch_shape(t, (int64_t)64 * 16 * K, kInFlightTarget);
     const int64_t threads = n >> 2;
     if (!grid_fits(threads, shape.block)) return DILOCO_ERR_SHAPE;
     Grid g = make_grid(t, threads, shape.block);
-    if (!grant_lds(&stream_rmw_kernel<K>, shape.lds)) return DILOCO_ERR_LAUNCH;
-    return launch(stream_rmw_kernel<K>, dim3(g.blocks), dim3(shape.block), shape.lds, st, base, stride, n, g.per_xcd);
+    if (!grant_lds(&stream_sweep_kernel<K, MODE>, shape.lds)) return DILOCO_ERR_LAUNCH;
+    return launch(stream_sweep_kernel<K, MODE>, dim3(g.blocks), dim3(shape.block), shape.lds, st, base, stride, n, fill,
+                  g.per_xcd);
+}
+template <int K>
+static int launch_sweep(float* base, int64_t stride, int64_t n, int mode, float fill, hipStream_t st,
+                        const Tuning& t) {
+    if (mode == 0) return launch_sweep_mode<K, 0>(base, stride, n, 0.f, st, t);
+    if (mode == 1) return launch_sweep_mode<K, 1>(base, stride, n, __builtin_nanf(""), st, t);
+    return launch_sweep_mode<K, 2>(base, stride, n, fill, st, t);
 }
 
 // Partial sums of the allocation-free loss: one copy of this array per GPU the library runs on,
@@ -213,8 +236,15 @@ extern "C" int diloco_sim_stream_copy(float* dst, const float* src, int64_t n, v
 
 extern "C" int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stride, void* stream,
                                      const diloco_launch* launch_arg) {
+    return diloco_sim_stream_sweep(base, K, n, stride, DILOCO_SIM_SWEEP_RMW, 0.f, stream, launch_arg);
+}
+
+extern "C" int diloco_sim_stream_sweep(float* base, int K, int64_t n, int64_t stride, int mode, float fill,
+                                       void* stream, const diloco_launch* launch_arg) {
     Tuning t;
     if (!resolve_launch(launch_arg, t)) return DILOCO_ERR_HYPER;
+    if (mode != DILOCO_SIM_SWEEP_RMW && mode != DILOCO_SIM_SWEEP_READ && mode != DILOCO_SIM_SWEEP_WRITE)
+        return DILOCO_ERR_DTYPE;
     if (!base) return DILOCO_ERR_NULL;
     if (n < 0 || (n & 3) || stride < n || K < 1) return DILOCO_ERR_SHAPE;
     if (stride > ((int64_t)1 << 50) / K) return DILOCO_ERR_SHAPE;
@@ -222,15 +252,15 @@ extern "C" int diloco_sim_stream_rmw(float* base, int K, int64_t n, int64_t stri
     if (n == 0) return DILOCO_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (K) {
-        case 1: return launch_rmw<1>(base, stride, n, st, t);
-        case 2: return launch_rmw<2>(base, stride, n, st, t);
-        case 4: return launch_rmw<4>(base, stride, n, st, t);
-        case 5: return launch_rmw<5>(base, stride, n, st, t);
-        case 8: return launch_rmw<8>(base, stride, n, st, t);
-        case 9: return launch_rmw<9>(base, stride, n, st, t);
-        case 16: return launch_rmw<16>(base, stride, n, st, t);
-        case 17: return launch_rmw<17>(base, stride, n, st, t);
-        case 33: return launch_rmw<33>(base, stride, n, st, t);
+        case 1: return launch_sweep<1>(base, stride, n, mode, fill, st, t);
+        case 2: return launch_sweep<2>(base, stride, n, mode, fill, st, t);
+        case 4: return launch_sweep<4>(base, stride, n, mode, fill, st, t);
+        case 5: return launch_sweep<5>(base, stride, n, mode, fill, st, t);
+        case 8: return launch_sweep<8>(base, stride, n, mode, fill, st, t);
+        case 9: return launch_sweep<9>(base, stride, n, mode, fill, st, t);
+        case 16: return launch_sweep<16>(base, stride, n, mode, fill, st, t);
+        case 17: return launch_sweep<17>(base, stride, n, mode, fill, st, t);
+        case 33: return launch_sweep<33>(base, stride, n, mode, fill, st, t);
         default: return DILOCO_ERR_SHAPE;
     }
 }

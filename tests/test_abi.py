@@ -163,6 +163,22 @@ def test_packed_state_validation(lib):
     assert f(st=P[1] + 4) == B.ERR_ALIGN          # the packed state must be 16-byte aligned
     assert f(st=P[0] + 16) == B.ERR_ALIAS
 
+    def pp(th=P[0], dt=0, M=2, n=64, stride=64, si=P[1], so=P[2], mu=0.9, var=0):
+        return lib.diloco_outer_eager_pingpong(th, dt, M, n, stride, si, so, 0.7, mu, 1, var, 1, None)
+    assert pp(n=0) == B.OK
+    assert pp(si=None) == B.ERR_NULL and pp(so=None) == B.ERR_NULL and pp(th=None) == B.ERR_NULL
+    assert pp(so=P[1]) == B.ERR_ALIAS                      # the same buffer twice: that is the in-place call
+    assert pp(so=P[1] + 4 * 8192) == B.ERR_ALIAS           # overlapping state buffers
+    assert pp(so=P[0] + 16) == B.ERR_ALIAS and pp(si=P[0] + 16) == B.ERR_ALIAS    # on top of theta
+    assert pp(so=P[2] + 4) == B.ERR_ALIGN and pp(si=P[1] + 8) == B.ERR_ALIGN
+    assert pp(mu=1.0) == B.ERR_HYPER and pp(var=2) == B.ERR_DTYPE and pp(M=0) == B.ERR_SHAPE
+    assert pp(n=0, var=B.EAGER | B.STATE_NO_MEAN | B.COMM_BF16) == B.OK
+    assert lib.diloco_outer_eager_pingpong_shaped(P[0], 0, 2, 0, 64, P[1], P[2], 0.7, 0.9, 1, 0, 1, None, None) == B.OK
+    assert lib.diloco_outer_eager_pingpong_shaped(P[0], 0, 2, 0, 64, P[1], P[2], 0.7, 0.9, 1, 0, 1, None,
+                                                  ctypes.byref(B.Launch(100, 0, 0, 0))) == B.ERR_HYPER
+    assert lib.diloco_outer_eager_pingpong_shaped(P[0], 0, 2, 64, 64, P[1], P[1], 0.7, 0.9, 1, 0, 1, None,
+                                                  None) == B.ERR_ALIAS
+
     def pk(st=P[0], M=2, n=64, a=P[1], u=P[2], pl=P[3], ss=64, pm=P[4], fn=None):
         return (fn or lib.diloco_pack_state)(st, M, n, a, u, pl, ss, pm, None)
     for fn in (lib.diloco_pack_state, lib.diloco_unpack_state):

@@ -214,6 +214,29 @@ def test_stream_rmw_leaves_the_rows_as_they_are(K):
             d.sim_stream_rmw(torch.zeros((3, 64), device=DEV))
 
 
+@pytest.mark.parametrize("K", [1, 5, 33])
+def test_stream_sweep_modes(K):
+    """The read-only sweep writes nothing, the write-only sweep fills exactly the first n elements of every row."""
+    n = 70_004
+    rows = torch.empty((K, n + 8), device=DEV).normal_()
+    before = rows.clone()
+    d.sim_stream_sweep(rows, d.SWEEP_READ, n=n)
+    d.sim_stream_sweep(rows, d.SWEEP_RMW, n=n, launch=(256, 1, 2))
+    torch.cuda.synchronize()
+    assert torch.equal(rows, before)
+    rows[0, 5] = float("nan")          # a NaN among the inputs must not make the read-only sweep write either
+    before = rows.clone()
+    d.sim_stream_sweep(rows, d.SWEEP_READ, n=n)
+    torch.cuda.synchronize()
+    assert torch.equal(rows.view(torch.int32), before.view(torch.int32))
+    d.sim_stream_sweep(rows, d.SWEEP_WRITE, n=n, fill=2.5)
+    torch.cuda.synchronize()
+    assert (rows[:, :n] == 2.5).all() and torch.equal(rows[:, n:], before[:, n:])
+    with pytest.raises(d.DilocoError) as ei:
+        d.sim_stream_sweep(rows, 3, n=n)
+    assert ei.value.status == d.binding.ERR_DTYPE
+
+
 def test_eager_empty_input_is_a_noop():
     wl = wl_for(2, 8)
     g = {k: v.to(DEV) for k, v in W.outer_state(wl, 8, seed=2).items()}
@@ -509,6 +532,70 @@ def test_eager_packed_against_the_checker_and_elementwise_path():
     torch.cuda.synchronize()
     for k in ref:
         assert_close(W.to_f64(g[k][..., :n]), ref[k], TOL_F32, f"packed {k}", scale=S[k])
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 8, 5, 9, 16, 33, 42])
+@pytest.mark.parametrize("n,pad", [(1, 0), (5, 3), (8191, 1), (8193, 0), (70_003, 1), (70_003, 2)])
+@pytest.mark.parametrize("flags", ["plain", "delayed", "no_mean+bf16", "fp4"])
+def test_eager_pingpong_walks_the_in_place_trajectory_bit_for_bit(M, n, pad, flags):
+    """Five boundaries (the first only records, so the velocities must be carried across) through
+    diloco_outer_eager_pingpong with two alternating state buffers against the in-place packed
+    call: theta after every boundary and the final state, bit for bit.  pad 2 gives theta an odd
+    row stride: the element-wise kernel."""
+    bf16 = (M + n) % 2 == 1
+    var = {"plain": d.EAGER, "delayed": d.DELAYED, "no_mean+bf16": d.EAGER | d.STATE_NO_MEAN | d.COMM_BF16,
+           "fp4": d.EAGER | d.COMM_EXMY(2, 1, 11)}[flags]
+    runs = []
+    for pingpong in (False, True):
+        g = _rows(M, n, 127, bf16, pad=pad)
+        g["vel"].normal_(0, 1e-3, generator=torch.Generator(device=DEV).manual_seed(5))   # must survive recording
+        states = [torch.full((d.packed_state_elems(M, n),), float("nan"), device=DEV) for _ in range(2)]
+        d.pack_state(states[0], M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
+                     prev_mean=g["prev_mean"])
+        thetas = []
+        cur = 0
+        for phase in range(5):
+            noise = W.normal((M, n), 1e-3, tag="theta_noise", seed=127, extra=phase, device=DEV)
+            g["theta"][:, :n] = (g["theta"][:, :n].float() + noise).to(g["theta"].dtype)
+            kw = dict(n=n, outer_lr=ETA, outer_momentum=MU, variant=var, apply_update=phase > 0)
+            if pingpong:
+                d.outer_eager_pingpong(g["theta"], states[cur], states[1 - cur], **kw)
+                cur = 1 - cur
+            else:
+                d.outer_eager_packed(g["theta"], states[0], **kw)
+            thetas.append(g["theta"].clone())
+        out = {k: torch.zeros_like(g[k]) for k in ("anchor", "vel", "prev_local", "prev_mean")}
+        d.unpack_state(states[cur], M, n, anchor=out["anchor"], vel=out["vel"], prev_local=out["prev_local"],
+                       prev_mean=None if "no_mean" in flags else out["prev_mean"])
+        torch.cuda.synchronize()
+        runs.append((thetas, out))
+    for a, b in zip(runs[0][0], runs[1][0]):
+        assert torch.equal(a, b)
+    for k in runs[0][1]:
+        assert torch.equal(runs[0][1][k], runs[1][1][k]), k
+        assert torch.isfinite(runs[1][1][k]).all(), k          # every stream of the fresh buffer was written
+
+
+def test_eager_pingpong_against_the_checker_and_refusals():
+    M, n = 8, 50_003
+    st = W.outer_state(wl_for(M, n), n, seed=131)
+    ref = {k: W.to_f64(v) for k, v in st.items()}
+    S = checked_eager(ref, ETA, MU)
+    g = {k: v.to(DEV) for k, v in st.items()}
+    a, b = (torch.zeros(d.packed_state_elems(M, n), device=DEV) for _ in range(2))
+    d.pack_state(a, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"], prev_mean=g["prev_mean"])
+    before = a.clone()
+    d.outer_eager_pingpong(g["theta"], a, b, outer_lr=ETA, outer_momentum=MU, launch=(256, 1, 2))
+    d.unpack_state(b, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"], prev_mean=g["prev_mean"])
+    torch.cuda.synchronize()
+    assert torch.equal(a, before)                               # the input state is read only
+    for k in ref:
+        assert_close(W.to_f64(g[k]), ref[k], TOL_F32, f"pingpong {k}", scale=S[k])
+    with pytest.raises(d.DilocoError) as ei:
+        d.outer_eager_pingpong(g["theta"], a, a, outer_lr=ETA, outer_momentum=MU)
+    assert ei.value.status == d.binding.ERR_ALIAS
+    with pytest.raises(ValueError):
+        d.outer_eager_pingpong(g["theta"], a, b[:-8192], outer_lr=ETA, outer_momentum=MU)
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -910,9 +997,14 @@ def test_seeded_sweep_of_valid_eager_calls_matches_the_checker(chunk):
                 state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
                 d.pack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
                              prev_mean=g["prev_mean"])
-                d.outer_eager_packed(g["theta"], state, **kw)
+                if (M + n) % 2 == 0:      # half of the packed cases: state read from one buffer, written to another
+                    state_out = torch.zeros_like(state)
+                    d.outer_eager_pingpong(g["theta"], state, state_out, **kw)
+                    state = state_out
+                else:
+                    d.outer_eager_packed(g["theta"], state, **kw)
                 d.unpack_state(state, M, n, anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"],
-                               prev_mean=g["prev_mean"])
+                               prev_mean=None if c["no_mean"] else g["prev_mean"])
             else:
                 d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], **kw)
         finally:
