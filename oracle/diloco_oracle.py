@@ -293,7 +293,7 @@ def is_boundary(t, H, offset=0):
 
 def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
                   lr, beta1, beta2, eps, weight_decay, eta, mu, nesterov=True,
-                  index_base=0, theta0=None, boundary_offset=0, overlap=1):
+                  index_base=0, theta0=None, boundary_offset=0, overlap=1, first_boundary="listing"):
     """T = H * phases steps of Algorithm 1 ("standard"), 2 ("delayed") or 3 ("eager")
     on the noisy quadratic, starting from theta = theta0 (default 0) on every replica.
     Outer boundaries fall on the steps t with t mod H == boundary_offset mod H (the listings
@@ -303,6 +303,12 @@ def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
     all-reduce launched at a boundary is consumed two boundaries later, i.e. Algorithms 2 and 3
     with Delta_m^(t-2H), Delta^(t-2H) in place of Delta_m^(t-H), Delta^(t-H) and `if t > 2H`;
     the two generations in flight live in two (P, D) slots used alternately.
+    first_boundary: "listing" follows Algorithms 2 and 3 to the letter (`if t > H`: nothing is
+    applied at the first boundary, the replica continues from its own parameters); "zero_history"
+    is the introduction's wording instead (the local outer gradient is used in an outer step before
+    the next phase starts): the outer step is applied at every boundary, the missing history being
+    zero (Delta_m^(0) = Delta^(0) = 0, so eager feeds Delta_m / M and delayed feeds 0).  Only under
+    zero history does an M = 1 eager run equal the standard run from the first phase on.
     Returns (state dict, losses) with losses[k] the loss after outer boundary k,
     evaluated at the replica mean of the outer parameters."""
     n = h.shape[0]
@@ -327,8 +333,9 @@ def run_quadratic(variant, M, H, phases, h, theta_star, seed, noise_std,
             else:
                 step = outer_eager if variant == "eager" else outer_delayed
                 slot = boundaries % overlap
+                assert first_boundary in ("listing", "zero_history")
                 step(theta, a, u, Ps[slot], Ds[slot], eta, mu, nesterov,
-                     apply_update=(boundaries > overlap))
+                     apply_update=(boundaries > overlap or first_boundary == "zero_history"))
                 losses.append(quadratic_loss(mean_over_replicas(a), h, theta_star))
     out = dict(theta=theta, a=a, u=u, P=Ps[0], D=Ds[0], m1=m1, m2=m2)
     if overlap > 1:

@@ -38,6 +38,8 @@ PINS = [
     P.test_reset_is_idempotent_and_broadcasts,
     lambda: P.test_mix64_matches_published_splitmix64_outputs(GOLDEN),
     P.test_noise_is_standard_normal_and_streams_are_independent,
+    P.test_noise_matches_a_hand_computation_of_its_definition,
+    P.test_noise_radius_and_angle_come_from_disjoint_bits,
     P.test_quadratic_gradient_and_loss_fixed_points,
     lambda: P.test_noise_free_quadratic_converges("eager"),
     P.test_quadratic_run_single_replica_standard_matches_torch_optimizers,
@@ -56,6 +58,7 @@ PINS = [
     lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_eager),
     lambda: P.test_quantised_communication_keeps_the_stale_share_identity(O.outer_delayed),
     S.test_checker_streaming_driver_reduces_to_the_plain_run,
+    P.test_zero_history_policy_of_the_driver,
 ]
 
 
@@ -232,6 +235,45 @@ def normal_ignores_replica(seed, t, m, idx):
     return ORIG["standard_normal"](seed, t, 0, idx)
 
 
+def _normal_with_fields(shift1, shift2, t_off=1, m_off=1, j_off=1, swap=False):
+    """The generator with its bit fields / counter offsets moved."""
+    def f(seed, t, m, idx):
+        idx = np.asarray(idx, dtype=np.int64)
+        U = np.uint64
+        G = U(0x9E3779B97F4A7C15)
+        with np.errstate(over="ignore"):
+            k0 = ORIG["mix64"](U(seed) + G * U(t + t_off))
+            key = ORIG["mix64"](k0 + G * U(m + m_off))
+            x = ORIG["mix64"](key + G * ((idx >> 1).astype(U) + U(j_off)))
+        f1 = ((x >> U(shift1)) & U(0xFFFFFF)).astype(np.float64)
+        f2 = ((x >> U(shift2)) & U(0xFFFFFF)).astype(np.float64)
+        if swap:
+            f1, f2 = f2, f1
+        r = np.sqrt(-2.0 * np.log((f1 + 1.0) / 16777216.0))
+        ang = 2.0 * np.pi * f2 / 16777216.0
+        return np.where((idx & 1) == 0, r * np.cos(ang), r * np.sin(ang))
+    return f
+
+
+normal_overlapping_fields = _normal_with_fields(40, 28)       # the angle reuses 12 bits of the radius
+normal_overlapping_fields.__name__ = "normal_overlapping_fields"
+normal_same_field_twice = _normal_with_fields(40, 40)
+normal_same_field_twice.__name__ = "normal_same_field_twice"
+normal_swapped_fields = _normal_with_fields(40, 16, swap=True)
+normal_swapped_fields.__name__ = "normal_swapped_fields"
+normal_low_bits = _normal_with_fields(24, 0)                  # bits 0-47 instead of 16-63
+normal_low_bits.__name__ = "normal_low_bits"
+normal_step_offset = _normal_with_fields(40, 16, t_off=0)     # t instead of t + 1 in the key
+normal_step_offset.__name__ = "normal_step_offset"
+normal_pair_offset = _normal_with_fields(40, 16, j_off=0)     # j instead of j + 1
+normal_pair_offset.__name__ = "normal_pair_offset"
+
+
+def normal_sine_first(seed, t, m, idx):
+    idx = np.asarray(idx, dtype=np.int64)
+    return ORIG["standard_normal"](seed, t, m, idx ^ 1)       # sine on the even element, cosine on the odd
+
+
 def bf16_truncates(x):
     bits = np.asarray(x, dtype=np.float32).view(np.uint32) & np.uint32(0xFFFF0000)
     return bits.view(np.float32).astype(np.float64)
@@ -287,6 +329,14 @@ def quadratic_gradient_without_curvature(theta_m, h, theta_star, noise_std, seed
     return (theta_m - theta_star) + noise_std * O.standard_normal(seed, t, m, idx)
 
 
+def run_quadratic_ignores_the_policy(*args, first_boundary="listing", **kw):
+    return ORIG["run_quadratic"](*args, **kw)
+
+
+def run_quadratic_always_zero_history(*args, first_boundary="listing", **kw):
+    return ORIG["run_quadratic"](*args, first_boundary="zero_history", **kw)
+
+
 ORIG = {k: getattr(O, k) for k in dir(O) if callable(getattr(O, k)) and not k.startswith("_")}
 
 MUTATIONS = [
@@ -305,13 +355,18 @@ MUTATIONS = [
     ("local_outer_gradients", local_wrong_sign), ("outer_standard", standard_no_reset),
     ("outer_standard", standard_ignores_wire_format),
     ("mix64", mix64_wrong_shift), ("standard_normal", normal_without_factor_two),
-    ("standard_normal", normal_ignores_replica), ("round_to_bf16", bf16_truncates),
+    ("standard_normal", normal_ignores_replica), ("standard_normal", normal_overlapping_fields),
+    ("standard_normal", normal_same_field_twice), ("standard_normal", normal_swapped_fields),
+    ("standard_normal", normal_low_bits), ("standard_normal", normal_step_offset),
+    ("standard_normal", normal_pair_offset), ("standard_normal", normal_sine_first),
+    ("round_to_bf16", bf16_truncates),
     ("is_boundary", boundary_ignores_offset),
     ("exmy_values", exmy_without_subnormals), ("exmy_values", exmy_ieee_top_exponent),
     ("round_to_exmy", exmy_truncates), ("round_to_exmy", exmy_ties_away),
     ("round_to_exmy", exmy_drops_sign), ("round_to_exmy", exmy_overflow_wraps_to_zero),
     ("sent_outer_gradients", sent_ignores_format),
     ("quadratic_gradient", quadratic_gradient_without_curvature),
+    ("run_quadratic", run_quadratic_ignores_the_policy), ("run_quadratic", run_quadratic_always_zero_history),
 ]
 
 

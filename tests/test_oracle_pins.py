@@ -7,6 +7,7 @@ the fresh local and all stale non-local outer gradients), reductions the
 listings imply (M = 1, identical replicas, stationary outer gradients), and
 published generator outputs.
 """
+import math
 import os
 
 import numpy as np
@@ -367,6 +368,101 @@ def test_noise_is_standard_normal_and_streams_are_independent():
     np.testing.assert_array_equal(O.standard_normal(123, 7, 2, idx[1001:1500]), z[1001:1500])
     # serial correlation
     assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 0.01
+
+
+def _z_by_hand(seed, t, m, i):
+    """z(seed, t, m, i) with Python integers and the math module only, one statement per clause of the
+    generator's definition in include/diloco_sim.h (no NumPy, no code shared with the checker)."""
+    mask = (1 << 64) - 1
+    G = 0x9E3779B97F4A7C15                                    # "the same odd constant"
+
+    def mix64(x):                                             # splitmix64's output function
+        x ^= x >> 30
+        x = (x * 0xBF58476D1CE4E5B9) & mask
+        x ^= x >> 27
+        x = (x * 0x94D049BB133111EB) & mask
+        x ^= x >> 31
+        return x
+    key = mix64((mix64((seed + (t + 1) * G) & mask) + (m + 1) * G) & mask)   # key = mix64(mix64(seed + (t+1) G) + (m+1) G)
+    j = i // 2                                                # elements 2j and 2j+1 share one word
+    x = mix64((key + (j + 1) * G) & mask)                     # x = mix64(key + (j+1) G)
+    u1 = ((x >> 40) + 1) / 2 ** 24                            # top 24 bits, in (0, 1]
+    u2 = ((x >> 16) & 0xFFFFFF) / 2 ** 24                     # next 24 bits, in [0, 1)
+    r = math.sqrt(-2.0 * math.log(u1))
+    return r * math.cos(2.0 * math.pi * u2) if i % 2 == 0 else r * math.sin(2.0 * math.pi * u2)
+
+
+def test_noise_matches_a_hand_computation_of_its_definition():
+    """A few coordinates, including the first and an odd index, a large step, a large index and a seed
+    that uses all 64 bits, against the definition evaluated with Python integers."""
+    cases = [(0, 0, 0, 0), (0, 0, 0, 1), (123, 7, 2, 1001), (0x5EEDD110C0, 2000, 3, (1 << 26) - 1),
+             (0xFEDCBA9876543210, 1, 65534, (1 << 33) + 4), (1, 31, 0, 2), (1, 31, 0, 3)]
+    for seed, t, m, i in cases:
+        got = float(O.standard_normal(seed, t, m, np.array([i]))[0])
+        want = _z_by_hand(seed, t, m, i)
+        assert abs(got - want) <= 1e-12 * max(1.0, abs(want)), (seed, t, m, i, got, want)
+    # both members of a pair come from one word: same radius
+    a, b = _z_by_hand(9, 4, 1, 10), _z_by_hand(9, 4, 1, 11)
+    pair = O.standard_normal(9, 4, 1, np.array([10, 11]))
+    assert abs((pair[0] ** 2 + pair[1] ** 2) - (a * a + b * b)) < 1e-12
+
+
+def test_noise_radius_and_angle_come_from_disjoint_bits():
+    """Radius and angle are recovered from the normals as 24-bit integers (exactly: float64 leaves
+    eight decimal digits to spare).  Every one of the 48 bits is balanced and no bit of the radius field
+    correlates with a bit of the angle field; fields that overlap, or a field used twice, would give
+    correlations of +-1 on the shared bits."""
+    n = 1 << 17
+    z = O.standard_normal(77, 3, 1, np.arange(2 * n))
+    r2 = z[0::2] ** 2 + z[1::2] ** 2
+    k1 = np.rint(np.exp(-r2 / 2.0) * 2.0 ** 24).astype(np.int64) - 1              # (x >> 40)
+    k2 = np.rint((np.arctan2(z[1::2], z[0::2]) / (2 * np.pi)) % 1.0 * 2.0 ** 24).astype(np.int64) % (1 << 24)
+    assert k1.min() >= 0 and k1.max() < (1 << 24) and k2.min() >= 0
+    # the recovery is exact: regenerating the normals from the integers gives them back
+    r = np.sqrt(-2.0 * np.log((k1 + 1) / 2.0 ** 24))
+    np.testing.assert_allclose(r * np.cos(2 * np.pi * k2 / 2.0 ** 24), z[0::2], rtol=0, atol=1e-9)
+    b1 = ((k1[:, None] >> np.arange(24)) & 1).astype(np.float64)
+    b2 = ((k2[:, None] >> np.arange(24)) & 1).astype(np.float64)
+    tol = 5.0 / np.sqrt(n)                                                        # five sigma
+    assert np.max(np.abs(b1.mean(axis=0) - 0.5)) < tol and np.max(np.abs(b2.mean(axis=0) - 0.5)) < tol
+    c = ((b1 - 0.5).T @ (b2 - 0.5)) / n * 4.0                                     # 24 x 24 bit correlations
+    assert np.max(np.abs(c)) < 1.2 * tol * 2, float(np.max(np.abs(c)))
+    within1 = ((b1 - 0.5).T @ (b1 - 0.5)) / n * 4.0 - np.eye(24)
+    assert np.max(np.abs(within1)) < 1.2 * tol * 2
+
+
+def test_zero_history_policy_of_the_driver():
+    """The driver's alternative first-boundary policy.  With one replica the eager rule under zero
+    history feeds Delta_1 itself at every boundary, so the whole run is standard DiLoCo (to rounding);
+    under the listing's policy the first phase differs.  With several replicas the first eager step
+    feeds Delta_m / M and the first delayed step feeds 0 (the replica returns to its start)."""
+    n, H, phases = 24, 4, 5
+    r = np.random.default_rng(17)
+    h, star = np.exp(r.uniform(np.log(1e-3), 0.0, n)), r.standard_normal(n)
+    kw = dict(seed=3, noise_std=0.1, lr=4e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, eta=0.7, mu=0.9)
+    std, std_loss = O.run_quadratic("standard", 1, H, phases, h, star, **kw)
+    zero, zero_loss = O.run_quadratic("eager", 1, H, phases, h, star, first_boundary="zero_history", **kw)
+    lit, lit_loss = O.run_quadratic("eager", 1, H, phases, h, star, **kw)
+    # (Delta - P)/1 + D with P = D is Delta up to one rounding of the difference
+    np.testing.assert_allclose(zero["a"][0], std["a"], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(zero["u"][0], std["u"], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(zero["theta"][0], std["theta"][0], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(zero_loss, std_loss, rtol=1e-12)
+    assert np.max(np.abs(lit["a"][0] - std["a"])) > 1e-6 and abs(lit_loss[0] / std_loss[0] - 1) > 1e-6
+    # first boundary with M = 3, by hand from the state after H inner steps
+    M = 3
+    for variant in ("eager", "delayed"):
+        one, _ = O.run_quadratic(variant, M, H, 1, h, star, first_boundary="zero_history", **kw)
+        ref, _ = O.run_quadratic(variant, M, H, 1, h, star, **kw)      # listing: a_m = theta_m^(H), nothing applied
+        delta = 0.0 - ref["a"]                                         # theta^(0) = 0: Delta_m = 0 - theta_m^(H)
+        G = delta / M if variant == "eager" else np.zeros_like(delta)
+        np.testing.assert_allclose(one["u"], G, rtol=0, atol=1e-18)    # u = mu * 0 + G
+        np.testing.assert_allclose(one["a"], 0.0 - 0.7 * (G + 0.9 * G), rtol=0, atol=1e-18)
+        np.testing.assert_array_equal(one["theta"], one["a"])
+        np.testing.assert_allclose(one["P"], delta, rtol=0, atol=0)
+        np.testing.assert_allclose(one["D"], delta.mean(axis=0), rtol=1e-15)
+    with pytest.raises(AssertionError):
+        O.run_quadratic("eager", 2, H, 1, h, star, first_boundary="sometimes", **kw)
 
 
 def test_quadratic_gradient_and_loss_fixed_points():
