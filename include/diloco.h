@@ -233,6 +233,24 @@ int diloco_outer_eager_pingpong(void* theta, diloco_dtype theta_dtype, int M, in
                                 double outer_lr, double outer_momentum, int nesterov,
                                 int variant, int apply_update, void* stream);
 
+/*
+ * Two-outer-steps overlap (Section 3.2, "Two-outer-steps overlap": the all-reduce launched at a
+ * boundary is consumed two boundaries later; the paper gives no formula, reading: Algorithms 2 / 3
+ * with Delta_m^(t-2H), Delta^(t-2H) in place of Delta_m^(t-H), Delta^(t-H) and `if t > 2H`) on
+ * the packed state.  Two packed buffers hold the two generations in flight.  At boundary b
+ * (1, 2, ...) the caller passes state_prev = the buffer written at boundary b-1 (its outer
+ * parameters and velocities are the current ones) and state_cur = the buffer written at boundary
+ * b-2 (its previous local / averaged outer gradients are the ones this step consumes); the call
+ * writes the complete new state to state_cur.  So the caller alternates: S[(b-1) % 2], S[b % 2].
+ * Both buffers start from the same packed state; apply_update == 0 at boundaries 1 and 2.
+ * DILOCO_STATE_NO_MEAN is refused (DILOCO_ERR_DTYPE); everything else as
+ * diloco_outer_eager_pingpong.
+ */
+int diloco_outer_eager_overlap2(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                int64_t stride, const float* state_prev, float* state_cur,
+                                double outer_lr, double outer_momentum, int nesterov,
+                                int variant, int apply_update, void* stream);
+
 /* theta_m <- outer parameters of replica m, read from the packed state. */
 int diloco_reset_packed(void* theta, diloco_dtype theta_dtype, int M, int64_t n, int64_t stride,
                         const float* state, void* stream);

@@ -81,6 +81,8 @@ SIGNATURES = {
                                              _c_int, _c_int, _c_int, _c_ptr]),
     "diloco_outer_eager_pingpong_shaped": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_dbl,
                                                     _c_dbl, _c_int, _c_int, _c_int, _c_ptr, _c_launch]),
+    "diloco_outer_eager_overlap2": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr, _c_dbl, _c_dbl,
+                                             _c_int, _c_int, _c_int, _c_ptr]),
     "diloco_reset_packed": (_c_int, [_c_ptr, _c_int, _c_int, _c_i64, _c_i64, _c_ptr, _c_ptr]),
     "diloco_stream_offset": (_c_i64, [_c_i64, _c_int, _c_int]),
     "diloco_stream_due": (_c_int, [_c_i64, _c_i64, _c_int, _c_int]),
@@ -373,6 +375,19 @@ def outer_eager_pingpong(theta, state_in, state_out, *, n=None, outer_lr, outer_
         _check("diloco_outer_eager_pingpong", lib().diloco_outer_eager_pingpong(*args))
     else:
         _check("diloco_outer_eager_pingpong_shaped", lib().diloco_outer_eager_pingpong_shaped(*args, _launch(launch)))
+
+
+def outer_eager_overlap2(theta, state_prev, state_cur, *, n=None, outer_lr, outer_momentum, nesterov=True,
+                         variant=EAGER, apply_update=True, stream=None) -> None:
+    """diloco_outer_eager_overlap2: 2-outer-steps overlap on two packed buffers; at boundary b pass the
+    buffer written at b-1 as state_prev and the one written at b-2 as state_cur (it is overwritten)."""
+    M, n = _shape_of(theta, n)
+    a = _packed_args("diloco_outer_eager_overlap2", state_prev, M, n)
+    a.vec(state_cur, "state_cur", packed_state_elems(M, n))
+    stride = a.rows(theta, "theta", M, n, _PARAM_DTYPES)
+    _check("diloco_outer_eager_overlap2", lib().diloco_outer_eager_overlap2(
+        _ptr(theta), _dtype_code(theta), M, n, stride, _ptr(state_prev), _ptr(state_cur), outer_lr, outer_momentum,
+        int(nesterov), int(variant), int(apply_update), _stream(stream)))
 
 
 def reset_packed(theta, state, *, n=None, stream=None) -> None:

@@ -93,16 +93,20 @@ struct RowState {
     __device__ __forceinline__ bool same_as(const RowState& o) const { return anchor == o.anchor; }
 };
 
+// `base` holds the outer parameters and velocities, `hist` the previous local and averaged outer
+// gradients: one and the same buffer, except when the call reads the two from different
+// generations of the state (2-outer-steps overlap).
 struct TiledState {
     float* base;
+    float* hist;
     int64_t M;  // replicas; streams per tile: 3M + 1
-    __device__ __forceinline__ float* at(int64_t s, int64_t i) const {
-        return base + ((((i >> kTileShift) * (3 * M + 1) + s) << kTileShift) | (i & (kTile - 1)));
+    __device__ __forceinline__ int64_t off(int64_t s, int64_t i) const {
+        return (((i >> kTileShift) * (3 * M + 1) + s) << kTileShift) | (i & (kTile - 1));
     }
-    __device__ __forceinline__ float* a(int m, int64_t i) const { return at(m, i); }
-    __device__ __forceinline__ float* d(int64_t i) const { return at(M, i); }
-    __device__ __forceinline__ float* u(int m, int64_t i) const { return at(M + 1 + 2 * m, i); }
-    __device__ __forceinline__ float* p(int m, int64_t i) const { return at(M + 2 + 2 * m, i); }
+    __device__ __forceinline__ float* a(int m, int64_t i) const { return base + off(m, i); }
+    __device__ __forceinline__ float* d(int64_t i) const { return hist + off(M, i); }
+    __device__ __forceinline__ float* u(int m, int64_t i) const { return base + off(M + 1 + 2 * m, i); }
+    __device__ __forceinline__ float* p(int m, int64_t i) const { return hist + off(M + 2 + 2 * m, i); }
     __device__ __forceinline__ bool same_as(const TiledState& o) const { return base == o.base; }
 };
 
@@ -765,9 +769,11 @@ static int outer_eager_impl(void* theta, int theta_dtype, int M, int64_t n, int6
 }
 
 // state_out == state: in place.  Otherwise the state is read from `state` and written to state_out.
+// hist_from_out: the previous local and averaged outer gradients are read from state_out (the
+// generation written two boundaries ago), the outer parameters and velocities from `state`.
 static int outer_eager_packed_impl(void* theta, int theta_dtype, int M, int64_t n, int64_t stride, float* state,
-                                   float* state_out, double outer_lr, double outer_momentum, int nesterov,
-                                   int variant, int apply_update, void* stream, const Tuning& t) {
+                                   float* state_out, bool hist_from_out, double outer_lr, double outer_momentum,
+                                   int nesterov, int variant, int apply_update, void* stream, const Tuning& t) {
     if (!theta || !state || !state_out) return DILOCO_ERR_NULL;
     if (!valid_dtype(theta_dtype)) return DILOCO_ERR_DTYPE;
     Variant v;
@@ -785,7 +791,7 @@ static int outer_eager_packed_impl(void* theta, int theta_dtype, int M, int64_t 
     if (n == 0) return DILOCO_OK;
     const bool vec_ok = aligned_to(theta, 4 * es) && (M == 1 || stride % 4 == 0);
     const OuterScalars sc = eager_scalars(M, outer_lr, outer_momentum, nesterov, v);
-    const TiledState sv{state, (int64_t)M}, so{state_out, (int64_t)M};
+    const TiledState sv{state, hist_from_out ? state_out : state, (int64_t)M}, so{state_out, state_out, (int64_t)M};
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int mode = mode_of(v.base, apply_update);
     if (theta_dtype == DILOCO_F32)
@@ -826,8 +832,18 @@ extern "C" int diloco_outer_eager_packed(void* theta, diloco_dtype theta_dtype, 
                                          int64_t stride, float* state, double outer_lr,
                                          double outer_momentum, int nesterov, int variant,
                                          int apply_update, void* stream) {
-    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, state, outer_lr, outer_momentum,
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, state, false, outer_lr, outer_momentum,
                                    nesterov, variant, apply_update, stream, tuning());
+}
+
+extern "C" int diloco_outer_eager_overlap2(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
+                                           int64_t stride, const float* state_prev, float* state_cur,
+                                           double outer_lr, double outer_momentum, int nesterov, int variant,
+                                           int apply_update, void* stream) {
+    if (state_prev == state_cur && state_prev) return DILOCO_ERR_ALIAS;
+    if (variant & DILOCO_STATE_NO_MEAN) return DILOCO_ERR_DTYPE;  // the mean of two boundaries ago is not at hand otherwise
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, const_cast<float*>(state_prev), state_cur, true,
+                                   outer_lr, outer_momentum, nesterov, variant, apply_update, stream, tuning());
 }
 
 extern "C" int diloco_outer_eager_pingpong(void* theta, diloco_dtype theta_dtype, int M, int64_t n,
@@ -835,7 +851,7 @@ extern "C" int diloco_outer_eager_pingpong(void* theta, diloco_dtype theta_dtype
                                            double outer_lr, double outer_momentum, int nesterov, int variant,
                                            int apply_update, void* stream) {
     if (state_in == state_out && state_in) return DILOCO_ERR_ALIAS;
-    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, const_cast<float*>(state_in), state_out,
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, const_cast<float*>(state_in), state_out, false,
                                    outer_lr, outer_momentum, nesterov, variant, apply_update, stream, tuning());
 }
 
@@ -847,7 +863,7 @@ extern "C" int diloco_outer_eager_pingpong_shaped(void* theta, diloco_dtype thet
     Tuning t;
     if (!resolve_launch(launch, t)) return DILOCO_ERR_HYPER;
     if (state_in == state_out && state_in) return DILOCO_ERR_ALIAS;
-    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, const_cast<float*>(state_in), state_out,
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, const_cast<float*>(state_in), state_out, false,
                                    outer_lr, outer_momentum, nesterov, variant, apply_update, stream, t);
 }
 
@@ -857,7 +873,7 @@ extern "C" int diloco_outer_eager_packed_shaped(void* theta, diloco_dtype theta_
                                                 int apply_update, void* stream, const diloco_launch* launch) {
     Tuning t;
     if (!resolve_launch(launch, t)) return DILOCO_ERR_HYPER;
-    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, state, outer_lr, outer_momentum,
+    return outer_eager_packed_impl(theta, theta_dtype, M, n, stride, state, state, false, outer_lr, outer_momentum,
                                    nesterov, variant, apply_update, stream, t);
 }
 

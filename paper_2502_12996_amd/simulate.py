@@ -6,7 +6,8 @@ lives here; every arithmetic step runs in the library's kernels:
     lines 3-5   diloco_sim_quadratic_inner   (gradient made in registers + AdamW, all replicas)
                 diloco_sim_quadratic_phase   (the same for all steps between two boundaries in one
                                               pass; --fused 1)
-    lines 7-12  diloco_outer_sync / diloco_outer_eager / diloco_outer_eager_packed
+    lines 7-12  diloco_outer_sync / diloco_outer_eager / diloco_outer_eager_packed /
+                diloco_outer_eager_pingpong / diloco_outer_eager_overlap2
     loss        diloco_sim_quadratic_loss    (at the replica mean of the outer parameters)
 
     python -m paper_2502_12996_amd.simulate            # benchmark configuration 5: 64M params,
@@ -28,9 +29,13 @@ from . import workloads as W
 class QuadraticSimulation:
     """M replicas training 0.5 sum_i h_i (theta_i - theta*_i)^2 with AdamW inside and one of the
     three outer rules outside.  variant: "standard" (Algorithm 1), "delayed" (Algorithm 2),
-    "eager" (Algorithm 3).  layout: "packed" or "rows" (outer state of Algorithms 2/3).
+    "eager" (Algorithm 3).  layout (outer state of Algorithms 2/3): "packed" (updated in place),
+    "pingpong" (two packed buffers, read one / write the other) or "rows".
     fragments: Streaming-DiLoCo windows [(offset, count), ...] on staggered boundaries.
-    overlap: 1 (the listings) or 2 (2-outer-steps overlap; rows layout only).
+    overlap: 1 (the listings) or 2 (2-outer-steps overlap: two generations of the previous outer
+    gradients, in two row sets or two packed buffers).
+    first_boundary: "listing" (Algorithms 2/3: no outer step at a fragment's first boundary) or
+    "zero_history" (the outer step is applied from the first boundary on, the history being zero).
     fused: run the inner steps between two outer boundaries as one pass over the buffers
     (bit-identical to the step-by-step run).
     no_mean: eager only, M <= 8: do not keep the previous mean, form it from the previous local
@@ -42,13 +47,17 @@ class QuadraticSimulation:
                  lr: float = 4e-4, beta1: float = 0.9, beta2: float = 0.95, eps: float = 1e-8,
                  weight_decay: float = 0.0, outer_lr: float = 0.7, outer_momentum: float = 0.9,
                  nesterov: bool = True, fused: bool = False, no_mean: bool = False,
-                 device: str = "cuda:0"):
+                 first_boundary: str = "listing", device: str = "cuda:0"):
         assert variant in ("standard", "delayed", "eager")
-        assert layout in ("packed", "rows") and overlap in (1, 2)
+        assert layout in ("packed", "pingpong", "rows") and overlap in (1, 2)
+        assert first_boundary in ("listing", "zero_history")
         self.M, self.n, self.H, self.variant = M, n, H, variant
         self.shared = variant == "standard"
-        self.packed = layout == "packed" and not self.shared
-        assert not (self.packed and overlap == 2), "the packed state holds one generation"
+        self.packed = layout != "rows" and not self.shared
+        self.pingpong = layout == "pingpong" and self.packed
+        assert not (self.pingpong and (overlap == 2 or fragments)), \
+            "ping-pong sweeps the whole model at every boundary, one generation in flight"
+        self.zero_history = first_boundary == "zero_history"
         self.fragments = list(fragments) if fragments else [(0, n)]
         self.overlap, self.seed, self.noise_std = overlap, seed, noise_std
         self.adam = dict(lr=lr, beta1=beta1, beta2=beta2, eps=eps, weight_decay=weight_decay)
@@ -70,6 +79,8 @@ class QuadraticSimulation:
             self.anchor, self.vel = torch.zeros(n, **f32), torch.zeros(n, **f32)
         elif self.packed:
             self.state = torch.zeros(B.packed_state_elems(M, n), **f32)
+            if self.pingpong or overlap == 2:             # the second packed buffer
+                self.states = [self.state, torch.zeros_like(self.state)]
             self.anchor = torch.zeros((M, ns), **f32)     # scratch for the loss only
         else:
             self.anchor, self.vel = torch.zeros((M, ns), **f32), torch.zeros((M, ns), **f32)
@@ -110,19 +121,36 @@ class QuadraticSimulation:
             th = self.theta[:, off:off + cnt]
             if self.shared:
                 B.outer_sync(th, self.anchor[off:off + cnt], self.vel[off:off + cnt], n=cnt, **self.outer)
+            elif self.packed and self.overlap == 2:
+                # the buffer written at this fragment's previous boundary, and the one written before that
+                prev, cur = self.states[(b - 1) % 2], self.states[b % 2]
+                B.outer_eager_overlap2(th, B.packed_window(prev, M, off), B.packed_window(cur, M, off), n=cnt,
+                                       variant=self.flags, apply_update=b > 2 or self.zero_history, **self.outer)
+            elif self.pingpong:
+                B.outer_eager_pingpong(th, self.states[(b - 1) % 2], self.states[b % 2], n=cnt, variant=self.flags,
+                                       apply_update=b > 1 or self.zero_history, **self.outer)
+                self.state = self.states[b % 2]
             elif self.packed:
                 B.outer_eager_packed(th, B.packed_window(self.state, M, off), n=cnt, variant=self.flags,
-                                     apply_update=b > 1, **self.outer)
+                                     apply_update=b > 1 or self.zero_history, **self.outer)
             else:
                 slot = b % self.overlap
                 B.outer_eager(th, self.anchor[:, off:off + cnt], self.vel[:, off:off + cnt],
                               self.prev_local[slot][:, off:off + cnt], self.prev_mean[slot][off:off + cnt],
-                              n=cnt, variant=self.flags, apply_update=b > self.overlap, **self.outer)
+                              n=cnt, variant=self.flags, apply_update=b > self.overlap or self.zero_history,
+                              **self.outer)
         return fired
 
     def outer_parameters(self) -> torch.Tensor:
         """[n] (standard) or [M, >= n] (delayed / eager) outer parameters."""
-        if self.packed:
+        if self.packed and self.overlap == 2:
+            # every fragment's current outer parameters sit in the buffer its last boundary wrote
+            F = len(self.fragments)
+            for f, (off, cnt) in enumerate(self.fragments):
+                b = B.stream_boundary_count(self.t, self.H, F, f)
+                B.unpack_state(B.packed_window(self.states[b % 2], self.M, off), self.M, cnt,
+                               anchor=self.anchor[:, off:off + cnt])
+        elif self.packed:
             B.unpack_state(self.state, self.M, self.n, anchor=self.anchor)
         return self.anchor
 
@@ -158,7 +186,7 @@ def main() -> None:
     ap.add_argument("--M", type=int, default=wl.M)
     ap.add_argument("--H", type=int, default=wl.H)
     ap.add_argument("--phases", type=int, default=wl.phases)
-    ap.add_argument("--layout", choices=("packed", "rows"), default="packed")
+    ap.add_argument("--layout", choices=("packed", "pingpong", "rows"), default="packed")
     ap.add_argument("--fused", type=int, default=0, help="1: inner steps between boundaries in one pass")
     args = ap.parse_args()
     runs = [("standard", 1.0), ("eager", 1.0), ("delayed", 1.0), ("delayed", 0.25)]

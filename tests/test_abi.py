@@ -179,6 +179,14 @@ def test_packed_state_validation(lib):
     assert lib.diloco_outer_eager_pingpong_shaped(P[0], 0, 2, 64, 64, P[1], P[1], 0.7, 0.9, 1, 0, 1, None,
                                                   None) == B.ERR_ALIAS
 
+    def o2(th=P[0], M=2, n=64, sp=P[1], sc=P[2], var=0):
+        return lib.diloco_outer_eager_overlap2(th, 0, M, n, 64, sp, sc, 0.7, 0.9, 1, var, 1, None)
+    assert o2(n=0) == B.OK and o2(n=0, var=B.DELAYED | B.COMM_BF16) == B.OK
+    assert o2(sp=None) == B.ERR_NULL and o2(sc=None) == B.ERR_NULL
+    assert o2(sc=P[1]) == B.ERR_ALIAS and o2(sc=P[0] + 16) == B.ERR_ALIAS
+    assert o2(var=B.EAGER | B.STATE_NO_MEAN) == B.ERR_DTYPE and o2(var=5) == B.ERR_DTYPE
+    assert o2(sc=P[2] + 4) == B.ERR_ALIGN and o2(M=0) == B.ERR_SHAPE
+
     def pk(st=P[0], M=2, n=64, a=P[1], u=P[2], pl=P[3], ss=64, pm=P[4], fn=None):
         return (fn or lib.diloco_pack_state)(st, M, n, a, u, pl, ss, pm, None)
     for fn in (lib.diloco_pack_state, lib.diloco_unpack_state):

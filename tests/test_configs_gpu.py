@@ -14,7 +14,7 @@ from oracle import diloco_oracle as O
 from paper_2502_12996_amd import workloads as W
 from tests.streamed import f64 as SF, stream_chunks
 from tests.util import (TOL_BF16, TOL_F32, assert_close, checked_adamw, checked_eager, checked_standard, rel_err,
-                        scaled_err)
+                        scaled_err, trajectory_tol)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -359,11 +359,11 @@ def test_quadratic_fused_phase_at_full_size_is_bit_identical():
 # ------------------------------------------------------------------ config 5: noisy quadratic
 QUAD_WINDOWS = [(0, 4096), ((1 << 25) + 4096, (1 << 25) + 8192)]
 # 2000 AdamW steps and 40 outer steps with fp32 state against float64 state, the noise drawn
-# through fp32 log / sincos: the per-step differences (a few 1e-7) are carried, and for the
-# delayed variant at the full outer learning rate amplified, by the dynamics (the paper lowers
-# that rate fourfold for stability, Section 3.2 "Number of inner steps").  The gate of this
-# trajectory is the loss curve (1e-4 per phase); the state is held to 1e-3.
-QUAD_STATE_TOL = 1e-3
+# through fp32 log / sincos: the per-step differences (a few 1e-7, bounded by 1e-6 per call) are
+# carried, and for the delayed variant at the full outer learning rate amplified, by the dynamics
+# (the paper lowers that rate fourfold for stability, Section 3.2 "Number of inner steps").  The
+# gate of this trajectory is the loss curve (1e-4 per phase); the state is held to the derived
+# trajectory tolerance 1e-6 sqrt(2000) / (1 - mu) = 4.5e-4 (tests/util.py: trajectory_tol).
 
 
 @pytest.mark.parametrize("variant,lr_div", [("standard", 1), ("eager", 1), ("delayed", 1), ("delayed", 4)])
@@ -371,6 +371,7 @@ def test_quadratic_forty_phases(variant, lr_div):
     wl = W.WORKLOADS["quadratic"]
     M, n, H = wl.M, wl.n, wl.H
     eta = wl.outer_lr / lr_div
+    state_tol = trajectory_tol(H * wl.phases, wl.outer_momentum)
     seed = W.BASE_SEED
     h = W.log_uniform((n,), 1e-3, 1.0, tag="h", device=DEV)
     star = W.normal((n,), 1.0, tag="theta_star", device=DEV)
@@ -421,8 +422,9 @@ def test_quadratic_forty_phases(variant, lr_div):
                            ("m1", m1[:, lo:hi], st["m1"]), ("m2", m2[:, lo:hi], st["m2"])):
             e = rel_err(f64(g), r)
             worst_state = max(worst_state, e)
-            assert e <= QUAD_STATE_TOL, f"{variant} window {w} {name}: {e:.2e}"
+            assert e <= state_tol, f"{variant} window {w} {name}: {e:.2e} above {state_tol:.2e}"
     # whole-buffer loss against the windows' loss scaled up: sampling error of 8192 elements
     np.testing.assert_allclose(losses, scaled, rtol=0.1)
     print(f"quadratic/{variant}/lr_div={lr_div}: loss {losses[0]:.4e} -> {losses[-1]:.4e}; worst window "
-          f"loss deviation {worst_loss:.2e}, worst state error after {H * wl.phases} steps {worst_state:.2e}")
+          f"loss deviation {worst_loss:.2e}, worst state error after {H * wl.phases} steps {worst_state:.2e} "
+          f"(tolerance {state_tol:.2e})")

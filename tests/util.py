@@ -47,6 +47,16 @@ def rel_err(got: np.ndarray, want: np.ndarray) -> float:
     return float(np.max(np.abs(got - want) / (np.abs(want) + rms)))
 
 
+def trajectory_tol(steps: int, outer_momentum: float) -> float:
+    """Tolerance of a whole run in which the checker keeps float64 state and the library stores float32
+    after every call.  Every call contributes an independent rounding error of at most TOL_F32 of its
+    scale (the per-call bound); over `steps` calls they add up like a random walk, sqrt(steps), and
+    the outer optimizer's momentum hands an error of its input on with gain 1 / (1 - mu).  The step
+    size is the BOUND of the per-call error, three to five times the typical one, which is the
+    estimate's headroom (measured: 0.24 of it on the 2000-step configuration)."""
+    return TOL_F32 * float(np.sqrt(max(1, steps))) / (1.0 - outer_momentum)
+
+
 def scaled_err(got: np.ndarray, want: np.ndarray, scale: np.ndarray) -> float:
     """max_i |got_i - want_i| / scale_i.  Where the scale is zero every term of the sum is zero and
     the result must be exact."""
