@@ -208,20 +208,25 @@ def main():
         def run_in_place(sh=None, **kw):
             d.outer_eager_packed(theta, state, n=n, launch=sh, **okw, **kw)
         shape_in_place = autotune(run_in_place) if args.autotune else shape_default
-        run_in_place(shape_in_place)
-        inplace_all = timed(lambda: run_in_place(shape_in_place), max(5, args.steps // 2))
-        if pingpong:
-            # the state is read from one buffer and written to the other; the two swap after every step
-            pair = [state, torch.empty_like(state)]
-            flip = [0]
+        # the same step with the state read from one buffer and written to the other (the two swap
+        # after every call): timed on its own beside the in-place call, or as the step's kernel
+        pair = [state, torch.empty_like(state)]
+        flip = [0]
 
-            def run_outer(sh=None, **kw):
-                d.outer_eager_pingpong(theta, pair[flip[0]], pair[1 - flip[0]], n=n, launch=sh, **okw, **kw)
-                flip[0] = 1 - flip[0]
-            run_outer()       # both buffers hold a full state from here on
-            shape_outer = autotune(run_outer) if args.autotune else shape_default
+        def run_pingpong(sh=None, **kw):
+            d.outer_eager_pingpong(theta, pair[flip[0]], pair[1 - flip[0]], n=n, launch=sh, **okw, **kw)
+            flip[0] = 1 - flip[0]
+        run_pingpong()        # both buffers hold a full state from here on
+        shape_pingpong = autotune(run_pingpong) if args.autotune else shape_default
+        if pingpong:
+            run_outer, shape_outer = run_pingpong, shape_pingpong
+            run_in_place(shape_in_place)
+            other_all = timed(lambda: run_in_place(shape_in_place), max(6, args.steps // 2))
         else:
             run_outer, shape_outer = run_in_place, shape_in_place
+            run_pingpong(shape_pingpong)
+            other_all = timed(lambda: run_pingpong(shape_pingpong), max(6, args.steps // 2))
+            state = pair[flip[0]]     # the buffer the last ping-pong call wrote: the current state
     else:
         run_outer, shape_outer = run_rows, shape_rows
 
@@ -396,7 +401,8 @@ def main():
         "outer_step_rows_layout": {"ms": rows_ms, "GBps": outer_bytes / (rows_ms * 1e-3) / 1e9,
                                    "frac_of_peak": outer_bytes / (rows_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                    "per_launch": rows_spread, "launch": shape_json(shape_rows)},
-        **({"outer_step_packed_in_place": dict(rates(inplace_all, outer_bytes), launch=shape_json(shape_in_place))}
+        **({("outer_step_packed_in_place" if pingpong else "outer_step_packed_pingpong"):
+            dict(rates(other_all, outer_bytes), launch=shape_json(shape_in_place if pingpong else shape_pingpong))}
            if packed else {}),
         "inner_step": {"ms": inner_ms, "worker_params_per_s": M * n / (inner_ms * 1e-3),
                        "GBps": inner_gbps, "frac_of_peak": inner_gbps / HBM_PEAK_GBPS, "per_step": inner_spread},
@@ -418,9 +424,7 @@ def main():
         result["roofline"]["traffic_GBps"] = result["roofline"]["traffic"] / (outer_ms * 1e-3) / 1e9
     del st, ad, theta, m1, m2, grad
     if packed:
-        del state
-        if pingpong:
-            del pair
+        del state, pair
     torch.cuda.empty_cache()
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample)
