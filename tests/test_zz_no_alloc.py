@@ -5,6 +5,8 @@ it must give the bits of diloco_sim_quadratic_loss on two calls in a row, the se
 input (the array then still holds the first call's partial sums beyond the second call's reach),
 and must not allocate device memory.
 """
+import gc
+
 import pytest
 import torch
 
@@ -23,6 +25,14 @@ def _problem(M, n, seed):
     return theta, h, star
 
 
+def _memory_picture():
+    """Device memory as the driver reports it, and torch's own requests to it (the slices of `got`
+    that the calls receive are views: they allocate nothing)."""
+    stats = torch.cuda.memory_stats()
+    return (torch.cuda.mem_get_info()[0], torch.cuda.memory_reserved(), torch.cuda.memory_allocated(),
+            stats["allocation.all.allocated"], stats["segment.all.allocated"])
+
+
 def test_static_loss_matches_the_workspace_entry_point_on_two_calls_in_a_row():
     assert torch.cuda.is_available()
     cases = [(4, (1 << 23) + 5, 11), (3, 70_001, 12)]          # 8192 partial sums, then 69
@@ -37,11 +47,18 @@ def test_static_loss_matches_the_workspace_entry_point_on_two_calls_in_a_row():
     d.sim_quadratic_loss_static(data[1][0], data[1][1], data[1][2], got[1:2], n=cases[1][1])   # first use: set-up
     torch.cuda.synchronize()
     got.fill_(-1.0)
-    before = torch.cuda.memory_allocated(), torch.cuda.memory_reserved(), torch.cuda.mem_get_info()[0]
-    for k, ((M, n, _), (theta, h, star)) in enumerate(zip(cases, data)):                       # large, then small
-        d.sim_quadratic_loss_static(theta, h, star, got[k:k + 1], n=n)
-    torch.cuda.synchronize()
-    after = torch.cuda.memory_allocated(), torch.cuda.memory_reserved(), torch.cuda.mem_get_info()[0]
+    # Tensors of earlier tests that the collector frees in between would move torch's byte counts:
+    # collect them first, keep the collector off meanwhile, and count allocation requests as well.
+    gc.collect()
+    gc.disable()
+    try:
+        before = _memory_picture()
+        for k, ((M, n, _), (theta, h, star)) in enumerate(zip(cases, data)):                   # large, then small
+            d.sim_quadratic_loss_static(theta, h, star, got[k:k + 1], n=n)
+        torch.cuda.synchronize()
+        after = _memory_picture()
+    finally:
+        gc.enable()
     assert before == after, "the call changed the device memory in use"
     assert torch.equal(got, want), (got, want)                                                 # same kernels: same bits
     # and against the checker, to the bar of the workspace entry point's own test
