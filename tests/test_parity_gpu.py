@@ -1087,6 +1087,127 @@ def test_the_one_element_draw_whose_velocity_cancels():
     assert abs(float(u32[0]) - ru[0]) / abs(ru[0]) > 5e-5
 
 
+# ------------------------------------------------------------------ non-finite values
+def _kind(x):
+    """0 finite, 1 NaN, 2 +Inf, 3 -Inf, element by element."""
+    x = np.asarray(x, dtype=np.float64)
+    return np.where(np.isnan(x), 1, np.where(np.isposinf(x), 2, np.where(np.isneginf(x), 3, 0)))
+
+
+def _same_kinds_and_close_where_finite(got, want, what):
+    kg, kw = _kind(got), _kind(want)
+    assert np.array_equal(kg, kw), f"{what}: NaN / Inf pattern {kg.tolist()} against the checker's {kw.tolist()}"
+    fin = kw == 0
+    np.testing.assert_allclose(np.asarray(got)[fin], np.asarray(want)[fin], rtol=1e-2, atol=1e-6, err_msg=what)
+
+
+# where the bad values go: inside a vector, first lane, the ragged tail; one index takes +Inf and -Inf
+# from two replicas (their sum is NaN)
+def _poison(theta, n):
+    M = theta.shape[0]
+    idx = sorted({0, 5, n // 2, n - 1})
+    vals = [float("nan"), float("inf"), float("-inf"), float("inf")]
+    for j, (i, v) in enumerate(zip(idx, vals)):
+        theta[j % M, i] = v
+    if M > 1:
+        theta[(len(idx) - 1 + 1) % M, idx[-1]] = float("-inf") if vals[len(idx) - 1] > 0 else float("inf")
+    return idx
+
+
+@pytest.mark.parametrize("M,n,bf16,misalign,packed", [(4, 1027, False, 0, False), (8, 4099, True, 0, True),
+                                                      (9, 1027, False, 0, False), (17, 263, False, 0, True),
+                                                      (3, 1027, False, 1, False), (1, 70, False, 0, False)])
+@pytest.mark.parametrize("variant,apply", [("eager", True), ("delayed", True), ("eager", False)])
+def test_non_finite_replica_values_stay_at_their_index(M, n, bf16, misalign, packed, variant, apply):
+    """A NaN or an infinity in a replica (a diverged run) must come out as the checker says at that
+    index (Nesterov form: same NaN / +Inf / -Inf pattern in every output buffer) and must not change
+    a bit at any other index."""
+    wl = wl_for(M, n, bf16)
+    var = d.EAGER if variant == "eager" else d.DELAYED
+    out = []
+    for poisoned in (False, True):
+        st = W.outer_state(wl, n, seed=91, stride=n + misalign)
+        if misalign:
+            st = {k: (v[:, misalign:] if v.dim() == 2 else v) for k, v in st.items()}
+        idx = _poison(st["theta"], n) if poisoned else None
+        ref = {k: W.to_f64(v[..., :n]) for k, v in st.items()}
+        with np.errstate(all="ignore"):
+            if variant == "eager":
+                O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"],
+                              ETA, MU, True, apply)
+            else:
+                O.outer_delayed(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"],
+                                ETA, MU, True, apply)
+        full = {k: v.to(DEV) for k, v in W.outer_state(wl, n, seed=91, stride=n + misalign).items()}
+        g = {k: (v[:, misalign:] if (misalign and v.dim() == 2) else v) for k, v in full.items()}
+        if poisoned:
+            g["theta"][:, :n] = st["theta"][:, :n].to(DEV)
+        if packed:
+            state = torch.zeros(d.packed_state_elems(M, n), device=DEV)
+            names = dict(anchor=g["anchor"], vel=g["vel"], prev_local=g["prev_local"], prev_mean=g["prev_mean"])
+            d.pack_state(state, M, n, **names)
+            d.outer_eager_packed(g["theta"], state, n=n, outer_lr=ETA, outer_momentum=MU, variant=var,
+                                 apply_update=apply)
+            d.unpack_state(state, M, n, **names)
+        else:
+            d.outer_eager(g["theta"], g["anchor"], g["vel"], g["prev_local"], g["prev_mean"], n=n,
+                          outer_lr=ETA, outer_momentum=MU, variant=var, apply_update=apply)
+        torch.cuda.synchronize()
+        out.append(({k: v[..., :n].clone() for k, v in g.items()}, ref, idx))
+    (clean, _, _), (bad, ref, idx) = out
+    keep = torch.ones(n, dtype=torch.bool, device=DEV)
+    keep[idx] = False
+    for k in clean:
+        assert torch.equal(clean[k][..., keep], bad[k][..., keep]), f"{k}: an index without a bad value changed"
+        _same_kinds_and_close_where_finite(W.to_f64(bad[k][..., idx]), ref[k][..., idx], f"{variant} {k}")
+    # the test plants something: the new mean holds NaN and infinities in both runs of the checker's pattern
+    assert set(_kind(ref["prev_mean"][idx]).tolist()) >= ({1, 3} if M > 1 else {1})
+
+
+def test_non_finite_values_in_the_standard_step_and_adamw():
+    M, n = 5, 1027
+    wl = wl_for(M, n)
+    # standard outer step: the shared outer parameters take the bad value at that index, every replica with them
+    outs = []
+    for poisoned in (False, True):
+        st = W.outer_state(wl, n, seed=93)
+        theta, a, u = st["theta"], st["anchor"][0].clone(), st["vel"][0].clone()
+        idx = _poison(theta, n) if poisoned else None
+        rt, ra, ru = W.to_f64(theta), W.to_f64(a), W.to_f64(u)
+        with np.errstate(all="ignore"):
+            rmean = O.outer_standard(rt, ra, ru, ETA, MU, True)
+        gt, ga, gu, gm = theta.to(DEV), a.to(DEV), u.to(DEV), torch.empty(n, device=DEV)
+        d.outer_sync(gt, ga, gu, mean_out=gm, outer_lr=ETA, outer_momentum=MU)
+        torch.cuda.synchronize()
+        outs.append((dict(theta=gt, anchor=ga, vel=gu, mean=gm), dict(theta=rt, anchor=ra, vel=ru, mean=rmean), idx))
+    (clean, _, _), (bad, ref, idx) = outs
+    keep = torch.ones(n, dtype=torch.bool, device=DEV)
+    keep[idx] = False
+    for k in clean:
+        assert torch.equal(clean[k][..., keep], bad[k][..., keep]), k
+        _same_kinds_and_close_where_finite(W.to_f64(bad[k][..., idx]), ref[k][..., idx], f"standard {k}")
+    assert (_kind(ref["anchor"][idx]) != 0).all()
+    # AdamW: a bad gradient value reaches theta_m, m1, m2 of its replica and index only
+    outs = []
+    for poisoned in (False, True):
+        st = W.adamw_state(wl, n, seed=95)
+        idx = _poison(st["grad"], n) if poisoned else None
+        ref = {k: W.to_f64(v) for k, v in st.items()}
+        with np.errstate(all="ignore"):
+            O.adamw_step(ref["theta"], ref["m1"], ref["m2"], ref["grad"], 7, wl.lr, wl.beta1, wl.beta2, wl.eps,
+                         wl.weight_decay)
+        g = {k: v.to(DEV) for k, v in st.items()}
+        d.inner_adamw(g["theta"], g["m1"], g["m2"], g["grad"], lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2,
+                      eps=wl.eps, weight_decay=wl.weight_decay, step=7)
+        torch.cuda.synchronize()
+        outs.append((g, ref, idx))
+    (clean, _, _), (bad, ref, idx) = outs
+    for k in ("theta", "m1", "m2"):
+        assert torch.equal(clean[k][..., keep], bad[k][..., keep]), k
+        _same_kinds_and_close_where_finite(W.to_f64(bad[k][..., idx]), ref[k][..., idx], f"adamw {k}")
+    assert (_kind(ref["theta"][:, idx]) != 0).sum() >= len(idx)
+
+
 # ------------------------------------------------------------------ HIP graph capture
 def test_a_captured_step_replays_to_the_same_bits():
     """The entry points only enqueue kernels on the caller's stream (no allocation, no
