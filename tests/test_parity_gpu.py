@@ -1208,6 +1208,32 @@ def test_non_finite_values_in_the_standard_step_and_adamw():
     assert (_kind(ref["theta"][:, idx]) != 0).sum() >= len(idx)
 
 
+@pytest.mark.parametrize("M,n,stride", [(2, 67, 68), (8, 4099, 4100), (9, 263, 264), (2, 67, 67)])
+def test_subnormal_outer_gradients_are_kept_exactly(M, n, stride):
+    """Below 2^-126 float32 underflows gradually; the kernels do not flush to zero.  With replicas and
+    outer parameters that are even multiples of 2^-149, line 7's differences and line 8's mean (M a
+    power of two, or the sum a multiple of M) are exact in float32 and in the checker alike: same bits."""
+    rng = np.random.default_rng(97)
+    unit = np.float64(2.0) ** -149
+    ka = 2 * M * rng.integers(1, 1 << 18, size=(M, n))
+    kt = 2 * M * rng.integers(1, 1 << 18, size=(M, n))
+    a64, t64 = ka * unit, kt * unit
+    ref = dict(theta=t64.copy(), anchor=a64.copy(), vel=np.zeros((M, n)), prev_local=np.zeros((M, n)),
+               prev_mean=np.zeros(n))
+    O.outer_eager(ref["theta"], ref["anchor"], ref["vel"], ref["prev_local"], ref["prev_mean"], ETA, MU, True, False)
+    assert (np.abs(ref["prev_local"]) < 2.0 ** -126).all() and (ref["prev_local"] != 0).any()
+    buf = {k: torch.zeros((M, stride), device=DEV) for k in ("theta", "anchor", "vel", "prev_local")}
+    buf["theta"][:, :n] = torch.from_numpy(t64.astype(np.float32)).to(DEV)
+    buf["anchor"][:, :n] = torch.from_numpy(a64.astype(np.float32)).to(DEV)
+    mean = torch.zeros(n, device=DEV)
+    d.outer_eager(buf["theta"], buf["anchor"], buf["vel"], buf["prev_local"], mean, n=n, outer_lr=ETA,
+                  outer_momentum=MU, apply_update=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(W.to_f64(buf["prev_local"][:, :n]), ref["prev_local"])
+    assert np.array_equal(W.to_f64(mean), ref["prev_mean"])
+    assert np.array_equal(W.to_f64(buf["anchor"][:, :n]), ref["anchor"])
+
+
 # ------------------------------------------------------------------ HIP graph capture
 def test_a_captured_step_replays_to_the_same_bits():
     """The entry points only enqueue kernels on the caller's stream (no allocation, no
