@@ -117,9 +117,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="t550m")
-    ap.add_argument("--layout", choices=("pingpong", "packed", "rows"), default="pingpong",
-                    help="outer state: library-packed tiles read from one buffer and written to a second "
-                         "(default), the same tiles updated in place, or caller rows [M][stride]")
+    ap.add_argument("--layout", choices=("pingpong", "packed", "rows"), default="packed",
+                    help="outer state: library-packed tiles updated in place (default), the same tiles read "
+                         "from one buffer and written to a second, or caller rows [M][stride]")
     ap.add_argument("--autotune", type=int, default=1,
                     help="pick workgroup size / XCD mapping per kernel before the warm-up (1) or keep defaults (0)")
     ap.add_argument("--pad", type=int, default=0, help="extra elements between replica rows")
