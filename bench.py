@@ -123,6 +123,10 @@ def main():
     ap.add_argument("--autotune", type=int, default=1,
                     help="pick workgroup size / XCD mapping per kernel before the warm-up (1) or keep defaults (0)")
     ap.add_argument("--pad", type=int, default=0, help="extra elements between replica rows")
+    ap.add_argument("--placement", choices=("classes", "plain"), default="classes",
+                    help="where the swept buffers lie in device memory: AdamW's four arrays in one memory class "
+                         "and the packed outer state in another (paper_2502_12996_amd/placement.py; falls back to "
+                         "plain when that fails), or plain torch allocations")
     ap.add_argument("--cpu-sample", type=int, default=1 << 24,
                     help="parameter indices the CPU checker is timed on (0: skip)")
     args = ap.parse_args()
@@ -142,12 +146,47 @@ def main():
     M, n = wl.M, wl.n
     stride = n + args.pad
     bf16 = wl.theta_dtype == "bf16"
-    st = W.outer_state(wl, n, device=dev, stride=stride)
+    packed = args.layout != "rows"
+    pingpong = args.layout == "pingpong"
+
+    # Which physical memory a buffer lies in moves these sweeps by several per cent (two streams read
+    # together run 5 % faster inside one memory class than across two): the arrays that one kernel
+    # streams together are placed in one class each, before anything else is allocated.
+    arena, placed = None, {}
+    placement = {"requested": args.placement, "used": False}
+    if args.placement == "classes":
+        try:
+            from paper_2502_12996_amd import placement as PL
+            arena = PL.Arena(device=0)
+            arena.classify()
+            rows_bytes = M * stride * (2 if bf16 else 4)
+            groups = [[("theta", rows_bytes), ("m1", rows_bytes), ("m2", rows_bytes), ("grad", rows_bytes)]]
+            if packed:
+                groups.append([("state", d.packed_state_elems(M, n) * 4)])
+            placed = arena.place(groups)
+            arena.release_rest()
+            placement = {"requested": "classes", "used": True, **arena.summary()}
+        except Exception as err:             # no placement on this machine: ordinary allocations
+            if arena is not None:
+                arena.close()
+            arena, placed = None, {}
+            placement = {"requested": "classes", "used": False, "reason": repr(err)}
+
+    def adopt(name, t):
+        """The generated tensor, moved into the buffer placed for it if there is one."""
+        if name not in placed:
+            return t
+        dst = placed[name].view(t.dtype).view(t.shape)
+        dst.copy_(t)
+        return dst
+
     ad = W.adamw_state(wl, n, device=dev, stride=stride,
                        grad_dtype=torch.bfloat16 if bf16 else torch.float32)
-    theta = st["theta"]                      # the replicas' live parameters serve both kernels
-    m1, m2, grad = ad["m1"], ad["m2"], ad["grad"]
-    del ad["theta"]
+    m1, m2, grad = adopt("m1", ad.pop("m1")), adopt("m2", ad.pop("m2")), adopt("grad", ad.pop("grad"))
+    del ad                                   # its theta is not used: the replicas' live parameters serve both kernels
+    torch.cuda.empty_cache()
+    st = W.outer_state(wl, n, device=dev, stride=stride)
+    st["theta"] = theta = adopt("theta", st["theta"])
     torch.cuda.empty_cache()
     okw = dict(outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum)
 
@@ -194,10 +233,9 @@ def main():
     rows_all = timed(lambda: run_rows(shape_rows), max(5, args.steps // 2))
     rows_ms = sum(rows_all) / len(rows_all)
 
-    packed = args.layout != "rows"
-    pingpong = args.layout == "pingpong"
     if packed:
-        state = torch.empty(d.packed_state_elems(M, n), dtype=torch.float32, device=dev)
+        state = (placed["state"].view(torch.float32) if "state" in placed
+                 else torch.empty(d.packed_state_elems(M, n), dtype=torch.float32, device=dev))
         d.pack_state(state, M, n, anchor=st["anchor"], vel=st["vel"], prev_local=st["prev_local"],
                      prev_mean=st["prev_mean"])
         torch.cuda.synchronize()
@@ -391,7 +429,7 @@ def main():
         "config": {"workload": f"{wl.name}: M={M} replicas x N={n} params, one AdamW sweep + one "
                                f"fused eager outer step per step",
                    "M": M, "N": n, "theta_dtype": wl.theta_dtype, "stride_pad": args.pad,
-                   "outer_state_layout": args.layout,
+                   "outer_state_layout": args.layout, "placement": placement,
                    "launch": {"outer": shape_json(shape_outer), "inner": shape_json(shape_inner)}},
         "whole_step": {"ms": ms_step, "params_per_s": n / (ms_step * 1e-3),
                        "what": "one AdamW sweep + one eager outer step, host clock over the timed steps"},
@@ -422,9 +460,12 @@ def main():
     }
     if result["roofline"]["traffic"]:   # counter bytes over this run's time: the rate the counters imply
         result["roofline"]["traffic_GBps"] = result["roofline"]["traffic"] / (outer_ms * 1e-3) / 1e9
-    del st, ad, theta, m1, m2, grad
+    del st, theta, m1, m2, grad, placed
     if packed:
         del state, pair
+    torch.cuda.synchronize()
+    if arena is not None:
+        arena.close()
     torch.cuda.empty_cache()
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample)

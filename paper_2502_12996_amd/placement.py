@@ -24,7 +24,8 @@ from typing import Dict, List, Optional, Sequence, Tuple
 
 CHUNK_BYTES = 2 << 30
 ALIGN_BYTES = 4096            # every placed buffer starts on such a boundary
-SAME_CLASS_MIN_GAIN = 0.025   # two read streams in one class run at least this much faster than across classes
+SAME_CLASS_MIN_GAIN = 0.03    # two read streams in one class run at least this much faster than across classes
+                              # (measured 4.3-4.8 %; rates inside one class spread by up to 2.5 %)
 CLASS_CHUNKS_MAX = 50         # no class holds more 2 GiB chunks than this (a third of 288 GB is 44.7)
 
 
@@ -88,6 +89,38 @@ def plan_groups(labels: Sequence[int], groups: Sequence[int]) -> List[List[int]]
                 break
         out.append(got)
     return out
+
+
+def label_chunks(n: int, measure, max_classes: int = 8, min_members: int = 5,
+                 class_max: int = CLASS_CHUNKS_MAX) -> Tuple[List[int], List[Dict[int, float]]]:
+    """Labels 0, 1, ... (-1: no class) for n chunks.  measure(ref, rest) returns the two-stream read rate
+    of chunk `ref` with every chunk of `rest`.  One reference per class: the first chunk without a
+    label; the chunks that run fast with it share its class.  A reference with which more chunks run
+    fast than a class can hold straddles two classes and gets -1, as do, in the end, the chunks of
+    classes with fewer than `min_members` members (straddling chunks, disturbed measurements).
+    Returns (labels, the rates of every round)."""
+    labels: List[Optional[int]] = [None] * n
+    history: List[Dict[int, float]] = []
+    classes = 0
+    while None in labels and classes < max_classes:
+        ref = labels.index(None)
+        rest = [k for k in range(n) if labels[k] is None and k != ref]
+        rates = measure(ref, rest) if rest else {}
+        history.append(rates)
+        _, same, _ = split_by_rate(rates)
+        if len(same) + 1 > class_max:
+            labels[ref] = -1
+            continue
+        labels[ref] = classes
+        for k in same:
+            labels[k] = classes
+        classes += 1
+    sizes: Dict[int, int] = {}
+    for lab in labels:
+        if lab is not None and lab >= 0:
+            sizes[lab] = sizes.get(lab, 0) + 1
+    keep = {c: i for i, c in enumerate(sorted(c for c, m in sizes.items() if m >= min(min_members, n)))}
+    return [keep.get(lab, -1) if lab is not None else -1 for lab in labels], history
 
 
 # ------------------------------------------------------------------ HIP virtual memory management
@@ -197,7 +230,9 @@ class Arena:
         """Reserve an address range and map the chunks into it, in order; returns its address."""
         size = len(chunks) * self.chunk
         va = ctypes.c_void_p()
-        self._check(self.hip.hipMemAddressReserve(ctypes.byref(va), size, 0, None, 0), "hipMemAddressReserve")
+        # aligned like a chunk, so that the page tables can describe a chunk by large fragments
+        self._check(self.hip.hipMemAddressReserve(ctypes.byref(va), size, self.chunk, None, 0),
+                    "hipMemAddressReserve")
         done = 0
         try:
             for slot, c in enumerate(chunks):
@@ -241,8 +276,10 @@ class Arena:
             best = ms if best is None or ms < best else best
         return 2.0 * self.chunk / best / 1e6
 
-    def classify(self, reps: int = 5, max_classes: int = 4) -> List[int]:
-        """Label every chunk with its class by timing it against one reference chunk per class."""
+    def classify(self, reps: int = 5, max_classes: int = 8, min_members: int = 5) -> List[int]:
+        """Label every chunk with its class by timing it against one reference chunk per class.  A class
+        of fewer than `min_members` chunks is noise (a chunk that straddles two classes, a disturbed
+        measurement): its chunks are labelled -1 like the straddling references."""
         from . import binding
         torch = self.torch
         if self.scan_va is None:
@@ -254,22 +291,11 @@ class Arena:
                 whole[k * self.chunk:(k + 1) * self.chunk].zero_()
             del whole
             torch.cuda.synchronize(self.device)
-            labels: List[Optional[int]] = [None] * n
-            classes = 0
-            while None in labels and classes < max_classes:
-                ref = labels.index(None)
-                rest = [k for k in range(n) if labels[k] is None and k != ref]
-                rates = {k: self._pair_rate(binding, ref, k, reps) for k in rest}
-                self.rates.append(rates)
-                thr, same, other = split_by_rate(rates)
-                if thr is None and len(rest) + 1 > CLASS_CHUNKS_MAX:
-                    labels[ref] = -1                 # more chunks than one class holds, yet no contrast: the
-                    continue                         # reference straddles two classes; take another one
-                labels[ref] = classes
-                for k in same:
-                    labels[k] = classes
-                classes += 1
-            self.labels = [-1 if lab is None else lab for lab in labels]
+            def measure(ref, rest):
+                return {k: self._pair_rate(binding, ref, k, reps) for k in rest}
+            self.labels, self.rates = label_chunks(
+                n, measure, max_classes, min_members,
+                CLASS_CHUNKS_MAX * max(1, CHUNK_BYTES // self.chunk))
         return self.labels
 
     # -- buffers
