@@ -312,7 +312,8 @@ class Arena:
         for g in groups:
             total = sum(-(-int(b) // ALIGN_BYTES) * ALIGN_BYTES for _, b in g)
             sizes.append(-(-total // self.chunk))
-        avail = [lab if i not in self.placed else None for i, lab in enumerate(self.labels)]
+        avail = [lab if (i not in self.placed and self.handles[i] is not None) else None
+                 for i, lab in enumerate(self.labels)]
         idx = [i for i, lab in enumerate(avail) if lab is not None]
         plan = plan_groups([avail[i] for i in idx], sizes)
         out: Dict[str, object] = {}
