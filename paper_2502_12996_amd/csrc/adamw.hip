@@ -225,7 +225,7 @@ template <typename PT, typename GT>
 static int launch_adamw(void* theta, void* m1, void* m2, const void* grad, int M, int64_t n,
                         int64_t stride, const AdamScalars& sc, bool vec_ok, hipStream_t st, const Tuning& t) {
     // a wavefront of the vector kernel loads theta, m1, m2 and the gradient of 256 parameters
-    const Shape shape = launch_shape(t, (int64_t)64 * 4 * (3 * sizeof(PT) + sizeof(GT)), kInFlightTarget);
+    const Shape shape = launch_shape(t, (int64_t)64 * 4 * (3 * sizeof(PT) + sizeof(GT)), kInFlightTarget, false);
     const int block = shape.block;
     const int64_t threads = vec_ok ? (n >> 2) + ((n & 3) ? 1 : 0) : n;
     if (!grid_fits(threads, block)) return DILOCO_ERR_SHAPE;
