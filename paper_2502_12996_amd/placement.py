@@ -1,6 +1,6 @@
 """Placement of caller buffers by memory class on MI355X (optional; the C ABI never allocates).
 
-Measured on this GPU: its 288 GB fall into three classes of about 96 GB (a third each; presumably
+Measured on this GPU: its 288 GiB fall into three classes of 96 GiB (a third each; presumably
 the ranks of the 12-high HBM3E stacks, which no interface names).  Two streams that are read
 together run about 5 % faster when both lie in one class than across two (7.2-7.4 against
 6.85-7.0 TB/s for two 2 GiB streams), writes behave the other way round, and the sweeps of this
@@ -26,7 +26,7 @@ CHUNK_BYTES = 2 << 30
 ALIGN_BYTES = 4096            # every placed buffer starts on such a boundary
 SAME_CLASS_MIN_GAIN = 0.03    # two read streams in one class run at least this much faster than across classes
                               # (measured 4.3-4.8 %; rates inside one class spread by up to 2.5 %)
-CLASS_CHUNKS_MAX = 50         # no class holds more 2 GiB chunks than this (a third of 288 GB is 44.7)
+CLASS_CHUNKS_MAX = 50         # no class holds more 2 GiB chunks than this (a third of 288 GiB is 48)
 
 
 class PlacementError(RuntimeError):
@@ -364,3 +364,32 @@ class Arena:
         return {"chunk_bytes": self.chunk, "chunks": len(self.labels),
                 "chunks_per_class": {str(k): v for k, v in sorted(counts.items())},
                 "placed_chunks": len(self.placed)}
+
+
+def main() -> None:
+    """python -m paper_2502_12996_amd.placement: take the free device memory, label its chunks, print the map."""
+    arena = Arena()
+    try:
+        labels = arena.classify()
+        print(f"{len(labels)} chunks of {arena.chunk >> 20} MiB; chunks per class: {arena.summary()['chunks_per_class']}")
+        print("classes in mapping order ('.' = set aside):",
+              "".join("abcdefgh"[lab] if 0 <= lab < 8 else "." for lab in labels))
+        for k, rates in enumerate(arena.rates):
+            thr, same, other = split_by_rate(rates)
+            vals = sorted(rates.values())
+            if not vals:
+                continue
+            if thr is None:
+                print(f"reference {k}: {len(vals)} chunks, one group, {vals[0]:.0f} .. {vals[len(vals) // 2]:.0f} .. "
+                      f"{vals[-1]:.0f} GB/s")
+            else:
+                fast = sorted(rates[c] for c in same)
+                slow = sorted(rates[c] for c in other)
+                print(f"reference {k}: {len(fast)} chunks read with it at {fast[0]:.0f} .. {fast[len(fast) // 2]:.0f} .. "
+                      f"{fast[-1]:.0f} GB/s, {len(slow)} at {slow[0]:.0f} .. {slow[len(slow) // 2]:.0f} .. {slow[-1]:.0f} GB/s")
+    finally:
+        arena.close()
+
+
+if __name__ == "__main__":
+    main()
