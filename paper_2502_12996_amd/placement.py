@@ -183,6 +183,7 @@ class Arena:
     arena.release_rest()                      # chunks not placed go back to the driver
     ... use bufs["theta"].view(torch.float32) ...
     arena.close()                             # after the last use of the tensors: unmaps and frees
+    (also a context manager: `with Arena() as arena: ...` closes on the way out)
     """
 
     def __init__(self, device: int = 0, chunk_bytes: int = CHUNK_BYTES, keep_free: int = 8 << 30,
@@ -356,6 +357,12 @@ class Arena:
                 self.hip.hipMemRelease(h)
                 self.handles[i] = None
         self.placed = set()
+
+    def __enter__(self) -> "Arena":
+        return self
+
+    def __exit__(self, *exc) -> None:
+        self.close()
 
     def summary(self) -> Dict[str, object]:
         counts: Dict[int, int] = {}
