@@ -173,7 +173,9 @@ def test_t150m_thirty_inner_steps_then_eager_outer_step():
 # a second set of device buffers, and EVERY index of every output buffer is then compared with the
 # checker, chunk by chunk (tests/streamed.py).  Nothing is sampled.
 FULL = ["t150m", "t550m", "t2b4_bf16"]
-PACKED_SHAPES = [None, (256, 0, 0), (64, 1, 3), (512, 1, 0), (256, 1, 1), (64, 0, 2), (64, 1, 4)]
+# the last entry runs through the ping-pong entry point (state read from one buffer, written to another)
+PACKED_SHAPES = [None, (256, 0, 0), (64, 1, 3), (512, 1, 0), (256, 1, 1), (64, 0, 2), (64, 1, 4), (128, 1, 1),
+                 (64, 1, 2), "pingpong"]
 
 
 def big_chunks(n, size=1 << 14):
@@ -233,7 +235,14 @@ def test_full_size_eager_outer_step_every_index(name):
         theta = inp["theta"]
         del inp
         torch.cuda.empty_cache()
-        d.outer_eager_packed(theta, state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum, launch=shape)
+        if shape == "pingpong":
+            fresh = torch.empty_like(state)
+            d.outer_eager_pingpong(theta, state, fresh, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum,
+                                   launch=(64, 1, 2))
+            state = fresh
+            del fresh
+        else:
+            d.outer_eager_packed(theta, state, outer_lr=wl.outer_lr, outer_momentum=wl.outer_momentum, launch=shape)
         torch.cuda.synchronize()
         assert torch.equal(theta, st["theta"]), shape
         for lo in range(0, n, win):
